@@ -1,0 +1,150 @@
+/*
+ * l2a.h -- C ABI of the L2A token-wise conditional attention layer for MI355X (gfx950).
+ *
+ * The layer (paper Sec. 3.1): every token takes causal sliding-window (Local) attention
+ *     s_t = softmax_j( scale <q_t, k_j> : 0 <= t - j <= W ) v_j            (Sec. 2, window mask)
+ * and only tokens whose router decision d_t = 1 also take full-prefix causal (Global) attention
+ *     a_t = softmax_j( scale <q_t, k_j> : j <= t ) v_j   if d_t = 1, else 0 (Sec. 2 Eq. Attn; Sec. 3.1 Eq. 4)
+ * merged additively
+ *     o_t = s_t + d_t a_t                                                    (Sec. 3.1 Eq. 5).
+ * The window holds the token itself and the W tokens before it (W + 1 keys).
+ *
+ * How it is computed (Sec. 3.2; App. C Alg. 1): the routed queries are compacted into dense
+ * tiles with their original positions kept (Q_idx); a tiled online-softmax kernel runs over
+ * those tiles only, masks with the original positions, and skips K/V tiles beyond a tile's
+ * largest position; outputs are scattered back.  The backward pass visits the routed
+ * queries only, reusing the saved log-sum-exp and Q_idx.
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller unless it is the l2a_params
+ *     struct (host).  The library keeps no state and allocates nothing; all work is enqueued
+ *     on the caller's stream (`stream` is a hipStream_t passed as void*; NULL = default
+ *     stream) and no call synchronises with the host.
+ *   - Tensors are contiguous, row-major:  q, O, dO, dq, S, A : [B, T, Hq, D];
+ *     k, v, dk, dv : [B, T, Hkv, D];  lse_* : [B, Hq, T] float.  Element type is bf16
+ *     (L2A_BF16, fp32 accumulation, D = 128) or float (L2A_FP32, D = 64 or 128).
+ *   - Grouped-query attention: query head h reads KV head h / G, G = Hq / Hkv.
+ *   - Log-sum-exp values are natural logs of sum_j exp(scale <q,k_j>).
+ *   - Return value: 0 on success, a negative L2A_ERR_* otherwise.  On an argument error
+ *     nothing is launched and no output is touched.
+ *   - Data pointers must be 16-byte aligned.
+ */
+#ifndef L2A_H_
+#define L2A_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { L2A_BF16 = 0, L2A_FP32 = 1 };
+
+enum {
+    L2A_FLAG_DENSE = 1,       /* every token is routed (d = 1 everywhere): the in-house dense causal
+                                 FlashAttention-style mode; mask and index arrays are ignored, may be NULL */
+    L2A_FLAG_SKIP_LOCAL = 2,  /* run the Global branch only:  O = d a  */
+    L2A_FLAG_SKIP_GLOBAL = 4, /* run the Local branch only:   O = s    */
+    L2A_FLAG_SCALAR = 1 << 16 /* bf16 only: use the scalar-FMA kernels instead of the matrix-core ones
+                                 (slow; for cross-checking) */
+};
+
+enum {
+    L2A_OK = 0,
+    L2A_ERR_NULL = -1,        /* a required pointer is NULL */
+    L2A_ERR_SHAPE = -2,       /* B, T < 1; Hq % Hkv != 0; W < 0; mask_heads not in {1, Hkv, Hq}; sizes overflow int32 rows */
+    L2A_ERR_UNSUPPORTED = -3, /* dtype / D combination or flag combination not built */
+    L2A_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than l2a_*_workspace_bytes() */
+    L2A_ERR_ALIGN = -5,       /* a data pointer is not 16-byte aligned */
+    L2A_ERR_LAUNCH = -6       /* the HIP runtime refused a launch (hipGetLastError) */
+};
+
+typedef struct l2a_params {
+    int32_t B, T, Hq, Hkv, D;
+    int32_t W;           /* local window: keys j with 0 <= t - j <= W                  (Sec. 2) */
+    int32_t mask_heads;  /* routing mask is [B, mask_heads, T]: 1 (shared by all heads, the paper's
+                            router emits one decision per token, Sec. 3.1 Eq. 3), Hkv, or Hq   */
+    int32_t dtype;       /* L2A_BF16 | L2A_FP32 */
+    int32_t flags;       /* L2A_FLAG_* */
+    float softmax_scale; /* multiplies <q,k>; the paper uses 1/sqrt(d) (Sec. 2 Eq. Attn) */
+} l2a_params;
+
+int l2a_version(void);
+const char* l2a_strerror(int code);
+
+/* Host-only, pure: scratch bytes each call needs (0 is possible; then workspace may be NULL). */
+size_t l2a_route_workspace_bytes(const l2a_params* p);
+size_t l2a_attn_workspace_bytes(const l2a_params* p, int backward);
+
+/* Number of int32 entries of kblk_first_row per (b, KV head): ceil(T / 64) + 1. */
+int32_t l2a_kblk_entries(int32_t T);
+
+/*
+ * Routing compaction: the preprocessing step of the sparse kernel (Sec. 3.2; App. C Alg. 1
+ * step 1; App. D.1 counts it in the kernel's time).  For each (b, KV head) builds the
+ * ascending list of routed query rows.  A row is a (position, head-in-group) pair coded
+ * pos * G + g, so the G query heads that share a KV head sit in the same dense tile.
+ *
+ *   mask            in  [B, mask_heads, T] uint8; any non-zero byte means d = 1
+ *   row_idx         out [B, Hkv, T*G] int32, ascending; entries at index >= count are -1
+ *   count           out [B, Hkv] int32, number of routed rows
+ *   kblk_first_row  out [B, Hkv, ceil(T/64)+1] int32; entry k = number of rows with pos < 64 k
+ *                       (so the last entry equals count); lets the backward pass find, for a
+ *                       block of keys, the first compacted row that can see it
+ * Results are bit-exact and unique.  With L2A_FLAG_DENSE the call is a no-op returning L2A_OK.
+ */
+int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
+                      int32_t* kblk_first_row, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Forward (Sec. 3.1 Eqs. 2, 4, 5; App. C Alg. 1).
+ *
+ *   q_loc,k_loc,v_loc  in  inputs of the Local branch
+ *   q_glb,k_glb,v_glb  in  inputs of the Global branch; may be the same pointers as *_loc (the
+ *                          paper's shared-projection variant) or different tensors (separate
+ *                          Local / Global modules)
+ *   row_idx,count,kblk_first_row  in  from l2a_route_compact (NULL allowed with L2A_FLAG_DENSE
+ *                          or L2A_FLAG_SKIP_GLOBAL)
+ *   O           out [B,T,Hq,D]  o = s + d a
+ *   lse_local   out [B,Hq,T]    (may be NULL with L2A_FLAG_SKIP_LOCAL)
+ *   lse_global  out [B,Hq,T]    -inf where d = 0 (may be NULL with L2A_FLAG_SKIP_GLOBAL)
+ *   S_opt       out optional [B,T,Hq,D]: s alone (needed by l2a_attn_bwd)
+ *   A_opt       out optional [B,T,Hq,D]: d a alone, zero where d = 0 (needed by l2a_attn_bwd)
+ */
+int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, const void* v_loc,
+                 const void* q_glb, const void* k_glb, const void* v_glb, const int32_t* row_idx,
+                 const int32_t* count, const int32_t* kblk_first_row, void* O, float* lse_local,
+                 float* lse_global, void* S_opt, void* A_opt, void* workspace, size_t workspace_bytes,
+                 void* stream);
+
+/*
+ * Backward (Sec. 3.2: gradients only for the active queries, reusing the saved log-sum-exp
+ * and Q_idx; the formulas are the standard softmax-attention gradient).  With g_t = dO_t for
+ * the Local branch and d_t dO_t for the Global branch (from Eq. 5):
+ *     p_tj = exp(scale <q_t,k_j> - lse(t)),  delta_t = <g_t, out_t>,
+ *     dv_j += p_tj g_t,  ds_tj = p_tj (<g_t, v_j> - delta_t),
+ *     dq_t += scale ds_tj k_j,  dk_j += scale ds_tj q_t      (dk, dv summed over the G heads of a group).
+ *
+ *   dO                in  [B,T,Hq,D]
+ *   S, A              in  branch outputs saved by the forward (S_opt, A_opt)
+ *   lse_local, lse_global  in  saved by the forward
+ *   dq_loc,dk_loc,dv_loc   out gradients w.r.t. the Local branch's inputs
+ *   dq_glb,dk_glb,dv_glb   out gradients w.r.t. the Global branch's inputs.  If a *_glb pointer
+ *                          equals its *_loc partner the two gradients are summed into that one
+ *                          buffer (shared projections); all three must then alias.
+ *                          Rows of dq_glb for tokens with d = 0 are zero.
+ *   delta_glb_opt     out optional [B,Hq,T] float: <dO_t, a_t>, the task-loss part of the
+ *                          router-score gradient (Sec. 3.3 Eq. 7); zero where d = 0
+ */
+int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const void* k_loc,
+                 const void* v_loc, const void* q_glb, const void* k_glb, const void* v_glb,
+                 const int32_t* row_idx, const int32_t* count, const int32_t* kblk_first_row, const void* S,
+                 const void* A, const float* lse_local, const float* lse_global, void* dq_loc, void* dk_loc,
+                 void* dv_loc, void* dq_glb, void* dk_glb, void* dv_glb, float* delta_glb_opt,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* L2A_H_ */

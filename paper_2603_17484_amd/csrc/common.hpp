@@ -1,0 +1,77 @@
+// Shared declarations of the L2A HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/l2a.h"
+
+namespace l2a {
+
+// Problem geometry handed to every kernel.
+struct Geom {
+    int B, T, Hq, Hkv, G, D, W;
+    float scale;       // softmax scale
+    float scale_log2;  // scale * log2(e)
+};
+
+// One branch of the layer as a kernel sees it.
+//   LOCAL : rows are all (pos, g) pairs in identity order, keys pos-W..pos
+//   GLOBAL: rows come from row_idx (or identity when dense), keys 0..pos
+struct RowSet {
+    const int32_t* row_idx;  // [B,Hkv,T*G] or nullptr = identity (dense / local)
+    const int32_t* count;    // [B,Hkv]     or nullptr = T*G rows
+    const int32_t* kblk_first_row;  // [B,Hkv,ceil(T/64)+1] or nullptr (identity: 64*k*G)
+    int local;               // 1: sliding-window branch
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? L2A_OK : L2A_ERR_LAUNCH; }
+
+// ---- route_compact.hip
+size_t route_workspace_bytes(const l2a_params& p);
+int route_compact(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
+                  int32_t* kblk_first_row, void* ws, hipStream_t st);
+
+// A forward branch kernel computes x = attention(row) for every row of `rs` and then
+//   main_out[row] = merge ? main_out[row] + x : x      (O)
+//   copy_out[row] = x                                   (S_opt / A_opt, optional)
+//   lse_out[row]  = log-sum-exp
+//   lse_fill[row] = -inf, zero_fill[row] = 0            (optional: what the other branch leaves
+//                                                        for tokens it never visits)
+struct FwdOut {
+    void* main_out;
+    void* copy_out;
+    float* lse_out;
+    float* lse_fill;
+    void* zero_fill;
+    int merge;
+};
+
+// ---- attn_simple.hip : straightforward scalar-FMA kernels (fp32 arithmetic, any element type)
+int simple_fwd(const Geom& g, int dtype, const RowSet& rs, const void* q, const void* k, const void* v,
+               const FwdOut& out, hipStream_t st);
+int simple_bwd_dq(const Geom& g, int dtype, const RowSet& rs, const void* q, const void* k, const void* v,
+                  const void* dO, const float* lse, float* delta, void* dq, int accumulate, hipStream_t st);
+// dk, dv of every key token; `sets` (1 or 2 row sets: local and/or global) accumulate into the same outputs
+int simple_bwd_dkdv(const Geom& g, int dtype, const RowSet* sets, int nsets, const void* q, const void* k,
+                    const void* v, const void* dO, const float* const* lse, const float* const* delta, void* dk,
+                    void* dv, hipStream_t st);
+
+// ---- util.hip
+int row_deltas(const Geom& g, int dtype, const void* dO, const void* S, const void* A, float* delta_l,
+               float* delta_g, hipStream_t st);
+int fill_zero(void* ptr, size_t bytes, hipStream_t st);
+int fill_f32(float* ptr, size_t n, float value, hipStream_t st);
+
+// ---- attn_fwd_bf16.hip / attn_bwd_bf16.hip : MFMA kernels (bf16, D = 128)
+int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const FwdOut& out,
+             hipStream_t st);
+int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,
+                const float* lse, float* delta, void* dq, int accumulate, hipStream_t st);
+int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* q, const void* k, const void* v,
+                  const void* dO, const float* const* lse, const float* const* delta, void* dk, void* dv,
+                  hipStream_t st);
+
+}  // namespace l2a

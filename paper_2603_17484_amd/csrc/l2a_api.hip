@@ -1,0 +1,223 @@
+// C ABI of the L2A layer: argument checks and the launch sequence of each call.
+// Every step of the layer runs in the kernels of this library; nothing here computes.
+#include "common.hpp"
+
+using namespace l2a;
+
+namespace {
+
+int check_params(const l2a_params* p) {
+    if (!p) return L2A_ERR_NULL;
+    if (p->B < 1 || p->T < 1 || p->Hq < 1 || p->Hkv < 1 || p->W < 0) return L2A_ERR_SHAPE;
+    if (p->Hq % p->Hkv != 0) return L2A_ERR_SHAPE;
+    const int G = p->Hq / p->Hkv;
+    if (p->mask_heads != 1 && p->mask_heads != p->Hkv && p->mask_heads != p->Hq) return L2A_ERR_SHAPE;
+    if ((long long)p->T * G > 0x7fffffffLL) return L2A_ERR_SHAPE;       // row codes pos*G+g are int32
+    if ((long long)p->B * p->Hkv > 65535) return L2A_ERR_SHAPE;         // grid.y
+    if ((long long)p->B * p->T * p->Hq * p->D > (1LL << 40)) return L2A_ERR_SHAPE;
+    if (G > 16) return L2A_ERR_UNSUPPORTED;
+    if (p->dtype != L2A_BF16 && p->dtype != L2A_FP32) return L2A_ERR_UNSUPPORTED;
+    if (p->D != 64 && p->D != 128) return L2A_ERR_UNSUPPORTED;
+    if ((p->flags & L2A_FLAG_SKIP_LOCAL) && (p->flags & L2A_FLAG_SKIP_GLOBAL)) return L2A_ERR_UNSUPPORTED;
+    if (!(p->softmax_scale > 0.f)) return L2A_ERR_SHAPE;
+    return L2A_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+Geom make_geom(const l2a_params& p) {
+    Geom g;
+    g.B = p.B; g.T = p.T; g.Hq = p.Hq; g.Hkv = p.Hkv; g.G = p.Hq / p.Hkv; g.D = p.D;
+    g.W = p.W < p.T ? p.W : p.T;  // a window reaching past token 0 is the whole prefix
+    g.scale = p.softmax_scale;
+    g.scale_log2 = p.softmax_scale * kLog2e;
+    return g;
+}
+
+bool use_mfma(const l2a_params& p) { return p.dtype == L2A_BF16 && p.D == 128 && !(p.flags & L2A_FLAG_SCALAR); }
+
+size_t elem_bytes(const l2a_params& p) { return p.dtype == L2A_BF16 ? 2 : 4; }
+size_t q_elems(const l2a_params& p) { return (size_t)p.B * p.T * p.Hq * p.D; }
+size_t stat_elems(const l2a_params& p) { return (size_t)p.B * p.Hq * p.T; }
+
+int fwd_branch(const l2a_params& p, const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v,
+               const FwdOut& out, hipStream_t st) {
+    return use_mfma(p) ? mfma_fwd(g, rs, q, k, v, out, st) : simple_fwd(g, p.dtype, rs, q, k, v, out, st);
+}
+
+int bwd_dq(const l2a_params& p, const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v,
+           const void* dO, const float* lse, float* delta, void* dq, int acc, hipStream_t st) {
+    return use_mfma(p) ? mfma_bwd_dq(g, rs, q, k, v, dO, lse, delta, dq, acc, st)
+                       : simple_bwd_dq(g, p.dtype, rs, q, k, v, dO, lse, delta, dq, acc, st);
+}
+
+int bwd_dkdv(const l2a_params& p, const Geom& g, const RowSet* sets, int n, const void* q, const void* k,
+             const void* v, const void* dO, const float* const* lse, const float* const* delta, void* dk, void* dv,
+             hipStream_t st) {
+    return use_mfma(p) ? mfma_bwd_dkdv(g, sets, n, q, k, v, dO, lse, delta, dk, dv, st)
+                       : simple_bwd_dkdv(g, p.dtype, sets, n, q, k, v, dO, lse, delta, dk, dv, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int l2a_version(void) { return 1; }
+
+const char* l2a_strerror(int code) {
+    switch (code) {
+        case L2A_OK: return "ok";
+        case L2A_ERR_NULL: return "a required pointer is NULL";
+        case L2A_ERR_SHAPE: return "invalid shape, window, mask_heads or scale";
+        case L2A_ERR_UNSUPPORTED: return "unsupported dtype / head size / flag or aliasing combination";
+        case L2A_ERR_WORKSPACE: return "workspace missing or too small";
+        case L2A_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
+        case L2A_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+        default: return "unknown error code";
+    }
+}
+
+int32_t l2a_kblk_entries(int32_t T) { return (T + 63) / 64 + 1; }
+
+size_t l2a_route_workspace_bytes(const l2a_params* p) {
+    if (check_params(p) != L2A_OK) return 0;
+    if (p->flags & L2A_FLAG_DENSE) return 0;
+    return route_workspace_bytes(*p);
+}
+
+size_t l2a_attn_workspace_bytes(const l2a_params* p, int backward) {
+    if (check_params(p) != L2A_OK) return 0;
+    if (!backward) return 0;
+    return 2 * sizeof(float) * stat_elems(*p);  // delta of each branch
+}
+
+int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
+                      int32_t* kblk_first_row, void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_params(p);
+    if (rc != L2A_OK) return rc;
+    if (p->flags & L2A_FLAG_DENSE) return L2A_OK;
+    if (!mask || !row_idx || !count || !kblk_first_row) return L2A_ERR_NULL;
+    if (!workspace || workspace_bytes < route_workspace_bytes(*p)) return L2A_ERR_WORKSPACE;
+    if (misaligned(row_idx) || misaligned(workspace)) return L2A_ERR_ALIGN;
+    return route_compact(*p, mask, row_idx, count, kblk_first_row, workspace, (hipStream_t)stream);
+}
+
+int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, const void* v_loc,
+                 const void* q_glb, const void* k_glb, const void* v_glb, const int32_t* row_idx,
+                 const int32_t* count, const int32_t* kblk_first_row, void* O, float* lse_local,
+                 float* lse_global, void* S_opt, void* A_opt, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    (void)kblk_first_row;
+    const int rc = check_params(p);
+    if (rc != L2A_OK) return rc;
+    const bool dense = p->flags & L2A_FLAG_DENSE;
+    const bool do_local = !(p->flags & L2A_FLAG_SKIP_LOCAL);
+    const bool do_global = !(p->flags & L2A_FLAG_SKIP_GLOBAL);
+    if (!O) return L2A_ERR_NULL;
+    if (do_local && (!q_loc || !k_loc || !v_loc || !lse_local)) return L2A_ERR_NULL;
+    if (do_global && (!q_glb || !k_glb || !v_glb || !lse_global)) return L2A_ERR_NULL;
+    if (do_global && !dense && (!row_idx || !count)) return L2A_ERR_NULL;
+    const void* ptrs[] = {q_loc, k_loc, v_loc, q_glb, k_glb, v_glb, O, S_opt, A_opt};
+    for (const void* x : ptrs)
+        if (x && misaligned(x)) return L2A_ERR_ALIGN;
+
+    hipStream_t st = (hipStream_t)stream;
+    const Geom g = make_geom(*p);
+    int r = L2A_OK;
+    if (do_local) {
+        const RowSet rs{nullptr, nullptr, nullptr, 1};
+        FwdOut out{O, S_opt, lse_local, nullptr, nullptr, 0};
+        if (do_global && !dense) {  // tokens the global branch never visits
+            out.lse_fill = lse_global;
+            out.zero_fill = A_opt;
+        }
+        if ((r = fwd_branch(*p, g, rs, q_loc, k_loc, v_loc, out, st)) != L2A_OK) return r;
+    }
+    if (do_global) {
+        if (!do_local && !dense) {
+            if ((r = fill_zero(O, q_elems(*p) * elem_bytes(*p), st)) != L2A_OK) return r;
+            if (A_opt && (r = fill_zero(A_opt, q_elems(*p) * elem_bytes(*p), st)) != L2A_OK) return r;
+            if ((r = fill_f32(lse_global, stat_elems(*p), -INFINITY, st)) != L2A_OK) return r;
+        }
+        const RowSet rs = dense ? RowSet{nullptr, nullptr, nullptr, 0} : RowSet{row_idx, count, kblk_first_row, 0};
+        const FwdOut out{O, A_opt, lse_global, nullptr, nullptr, do_local ? 1 : 0};
+        if ((r = fwd_branch(*p, g, rs, q_glb, k_glb, v_glb, out, st)) != L2A_OK) return r;
+    }
+    return L2A_OK;
+}
+
+int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const void* k_loc,
+                 const void* v_loc, const void* q_glb, const void* k_glb, const void* v_glb,
+                 const int32_t* row_idx, const int32_t* count, const int32_t* kblk_first_row, const void* S,
+                 const void* A, const float* lse_local, const float* lse_global, void* dq_loc, void* dk_loc,
+                 void* dv_loc, void* dq_glb, void* dk_glb, void* dv_glb, float* delta_glb_opt,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_params(p);
+    if (rc != L2A_OK) return rc;
+    const bool dense = p->flags & L2A_FLAG_DENSE;
+    const bool do_local = !(p->flags & L2A_FLAG_SKIP_LOCAL);
+    const bool do_global = !(p->flags & L2A_FLAG_SKIP_GLOBAL);
+    if (!dO) return L2A_ERR_NULL;
+    if (do_local && (!q_loc || !k_loc || !v_loc || !S || !lse_local || !dq_loc || !dk_loc || !dv_loc))
+        return L2A_ERR_NULL;
+    if (do_global && (!q_glb || !k_glb || !v_glb || !A || !lse_global || !dq_glb || !dk_glb || !dv_glb))
+        return L2A_ERR_NULL;
+    if (do_global && !dense && (!row_idx || !count || !kblk_first_row)) return L2A_ERR_NULL;
+    if (!workspace || workspace_bytes < l2a_attn_workspace_bytes(p, 1)) return L2A_ERR_WORKSPACE;
+    const void* ptrs[] = {dO, q_loc, k_loc, v_loc, q_glb, k_glb, v_glb, S, A, dq_loc, dk_loc, dv_loc,
+                          dq_glb, dk_glb, dv_glb, workspace};
+    for (const void* x : ptrs)
+        if (x && misaligned(x)) return L2A_ERR_ALIGN;
+
+    const bool both = do_local && do_global;
+    const bool out_alias = both && dq_glb == dq_loc;
+    if (both && ((dk_glb == dk_loc) != out_alias || (dv_glb == dv_loc) != out_alias)) return L2A_ERR_UNSUPPORTED;
+    const bool in_alias = both && q_glb == q_loc && k_glb == k_loc && v_glb == v_loc;
+    if (out_alias && !in_alias) return L2A_ERR_UNSUPPORTED;  // summed gradients need shared inputs
+
+    hipStream_t st = (hipStream_t)stream;
+    const Geom g = make_geom(*p);
+    float* delta_l = (float*)workspace;
+    float* delta_g = delta_glb_opt ? delta_glb_opt : delta_l + stat_elems(*p);
+    int r;
+    if ((r = row_deltas(g, p->dtype, dO, do_local ? S : nullptr, do_global ? A : nullptr, delta_l, delta_g, st)) !=
+        L2A_OK)
+        return r;
+
+    const RowSet rs_l{nullptr, nullptr, nullptr, 1};
+    const RowSet rs_g = dense ? RowSet{nullptr, nullptr, nullptr, 0} : RowSet{row_idx, count, kblk_first_row, 0};
+
+    // dQ: one pass per branch over that branch's rows
+    if (do_local && (r = bwd_dq(*p, g, rs_l, q_loc, k_loc, v_loc, dO, lse_local, delta_l, dq_loc, 0, st)) != L2A_OK)
+        return r;
+    if (do_global) {
+        if (!out_alias && !dense && (r = fill_zero(dq_glb, q_elems(*p) * elem_bytes(*p), st)) != L2A_OK) return r;
+        if ((r = bwd_dq(*p, g, rs_g, q_glb, k_glb, v_glb, dO, lse_global, delta_g, dq_glb, out_alias ? 1 : 0, st)) !=
+            L2A_OK)
+            return r;
+    }
+    // dK, dV: one pass over the key tokens; with shared inputs both branches accumulate in registers
+    if (out_alias) {
+        const RowSet sets[2] = {rs_l, rs_g};
+        const float* lses[2] = {lse_local, lse_global};
+        const float* deltas[2] = {delta_l, delta_g};
+        return bwd_dkdv(*p, g, sets, 2, q_loc, k_loc, v_loc, dO, lses, deltas, dk_loc, dv_loc, st);
+    }
+    if (do_local) {
+        const float* lses[1] = {lse_local};
+        const float* deltas[1] = {delta_l};
+        if ((r = bwd_dkdv(*p, g, &rs_l, 1, q_loc, k_loc, v_loc, dO, lses, deltas, dk_loc, dv_loc, st)) != L2A_OK)
+            return r;
+    }
+    if (do_global) {
+        const float* lses[1] = {lse_global};
+        const float* deltas[1] = {delta_g};
+        if ((r = bwd_dkdv(*p, g, &rs_g, 1, q_glb, k_glb, v_glb, dO, lses, deltas, dk_glb, dv_glb, st)) != L2A_OK)
+            return r;
+    }
+    return L2A_OK;
+}
+
+}  // extern "C"

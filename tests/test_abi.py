@@ -1,0 +1,97 @@
+"""Host-side checks of the C-ABI library (no GPU work): it loads, exports every function the
+header declares, and turns bad arguments into error codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_17484_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2603_17484_amd.build import build_lib
+        build_lib()
+    return B.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "l2a.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(l2a_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(B.EXPORTS) == set(names), (names, B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert lib.l2a_version() == 1
+    assert lib.l2a_strerror(0) == b"ok" and b"NULL" in lib.l2a_strerror(-1)
+
+
+def test_params_struct_layout_matches_header():
+    assert ctypes.sizeof(B.l2a_params) == 40
+    assert [f[0] for f in B.l2a_params._fields_] == ["B", "T", "Hq", "Hkv", "D", "W", "mask_heads", "dtype",
+                                                     "flags", "softmax_scale"]
+
+
+def test_workspace_queries(lib):
+    p = B.make_params(1, 131072, 28, 4, 128, 4096, 28)
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 0) == 0
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * 4 * 28 * 131072
+    assert lib.l2a_route_workspace_bytes(ctypes.byref(p)) == 4 * 4 * (131072 // 2048)
+    assert lib.l2a_kblk_entries(131072) == 2049 and lib.l2a_kblk_entries(65) == 3
+    p.flags = B.L2A_FLAG_DENSE
+    assert lib.l2a_route_workspace_bytes(ctypes.byref(p)) == 0
+
+
+BAD = [
+    (dict(B=0), -2), (dict(T=0), -2), (dict(Hq=6, Hkv=4), -2), (dict(W=-1), -2), (dict(mask_heads=3), -2),
+    (dict(D=96), -3), (dict(dtype=7), -3), (dict(flags=B.L2A_FLAG_SKIP_LOCAL | B.L2A_FLAG_SKIP_GLOBAL), -3),
+    (dict(softmax_scale=0.0), -2), (dict(Hq=64, Hkv=2), -3),
+]
+
+
+@pytest.mark.parametrize("change,code", BAD)
+def test_bad_params_are_rejected_before_launch(lib, change, code):
+    kw = dict(B=1, T=256, Hq=4, Hkv=2, D=128, W=16, mask_heads=1, dtype=B.L2A_BF16, flags=0, softmax_scale=0.1)
+    kw.update(change)
+    p = B.l2a_params(*[kw[f[0]] for f in B.l2a_params._fields_])
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: validation fails first
+    assert lib.l2a_route_compact(ctypes.byref(p), fake, fake, fake, fake, fake, 1 << 20, None) == code
+    assert lib.l2a_attn_fwd(ctypes.byref(p), *([fake] * 14), None, 0, None) == code
+    assert lib.l2a_attn_bwd(ctypes.byref(p), *([fake] * 20), None, fake, 1 << 30, None) == code
+
+
+def test_null_alignment_and_workspace_errors(lib):
+    p = B.make_params(1, 256, 4, 2, 128, 16)
+    ok = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    pp = ctypes.byref(p)
+    assert lib.l2a_route_compact(None, ok, ok, ok, ok, ok, 64, None) == -1
+    assert lib.l2a_route_compact(pp, None, ok, ok, ok, ok, 64, None) == -1
+    assert lib.l2a_route_compact(pp, ok, ok, ok, ok, None, 0, None) == -4
+    assert lib.l2a_route_compact(pp, ok, ok, ok, ok, ok, 1, None) == -4
+    assert lib.l2a_route_compact(pp, ok, odd, ok, ok, ok, 64, None) == -5
+    fwd = [ok] * 14
+    assert lib.l2a_attn_fwd(pp, *(fwd[:9] + [None] + fwd[10:]), None, 0, None) == -1          # O missing
+    assert lib.l2a_attn_fwd(pp, *(fwd[:6] + [None] + fwd[7:]), None, 0, None) == -1           # row_idx missing
+    assert lib.l2a_attn_fwd(pp, *([odd] + fwd[1:]), None, 0, None) == -5
+    bwd = [ok] * 20
+    assert lib.l2a_attn_bwd(pp, *bwd, None, None, 0, None) == -4
+    assert lib.l2a_attn_bwd(pp, *bwd, None, ok, 8, None) == -4
+    assert lib.l2a_attn_bwd(pp, *([None] + bwd[1:]), None, ok, 1 << 30, None) == -1
+    # gradient buffers that alias only partly, or alias while the inputs differ, are refused
+    a, b2 = ctypes.c_void_p(0x2000), ctypes.c_void_p(0x3000)
+    part = bwd[:14] + [a, a, a, a, b2, b2]
+    assert lib.l2a_attn_bwd(pp, *part, None, ok, 1 << 30, None) == -3
+    diff_in = [ok, ok, ok, ok, a, a, a] + bwd[7:14] + [b2] * 6
+    assert lib.l2a_attn_bwd(pp, *diff_in, None, ok, 1 << 30, None) == -3
+    # dense mode needs no index arrays and no compaction work
+    p.flags = B.L2A_FLAG_DENSE
+    assert lib.l2a_route_compact(ctypes.byref(p), None, None, None, None, None, 0, None) == 0
