@@ -17,7 +17,7 @@
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer owned by the caller unless it is the l2a_params
- *     struct (host).  The library keeps no state and allocates nothing; all work is enqueued
+ *     struct (host).  The library allocates no device memory and keeps no state between calls; all work is enqueued
  *     on the caller's stream (`stream` is a hipStream_t passed as void*; NULL = default
  *     stream) and no call synchronises with the host.
  *   - Tensors are contiguous, row-major:  q, O, dO, dq, S, A : [B, T, Hq, D];
@@ -143,6 +143,20 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
                  const void* A, const float* lse_local, const float* lse_global, void* dq_loc, void* dk_loc,
                  void* dv_loc, void* dq_glb, void* dk_glb, void* dv_glb, float* delta_glb_opt,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Optional per-kernel timing, for benchmarks (not thread safe; off by default).  While enabled,
+ * every kernel the library launches is bracketed by HIP events on the launch stream.
+ * l2a_profile_read synchronises with those events, copies up to `max` records (launch order;
+ * `name` points to a static string) into `out`, clears the log and returns the number of
+ * records there were.  This log is the only state the library keeps between calls.
+ */
+typedef struct l2a_kernel_time {
+    const char* name;
+    float ms;
+} l2a_kernel_time;
+void l2a_profile_enable(int on);
+int l2a_profile_read(l2a_kernel_time* out, int max);
 
 #ifdef __cplusplus
 }

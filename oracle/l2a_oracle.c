@@ -28,6 +28,7 @@
  *     one list per (batch, KV head); kblk_first_row[k] counts rows with pos < 64 k.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -237,3 +238,6 @@ void l2a_oracle_bwd_dkdv_keys(const oracle_dims* p, const float* ql, const float
 }
 
 int l2a_oracle_abi(void) { return 1; }
+
+/* OpenMP threads the parallel loops above will use (for reporting timings). */
+int l2a_oracle_threads(void) { return omp_get_max_threads(); }

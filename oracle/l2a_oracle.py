@@ -50,6 +50,11 @@ def _load():
     return _lib
 
 
+def threads() -> int:
+    """OpenMP threads the oracle's loops use."""
+    return int(_load().l2a_oracle_threads())
+
+
 def _p(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 

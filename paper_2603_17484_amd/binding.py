@@ -21,7 +21,8 @@ L2A_FLAG_DENSE, L2A_FLAG_SKIP_LOCAL, L2A_FLAG_SKIP_GLOBAL = 1, 2, 4
 L2A_FLAG_SCALAR = 1 << 16
 
 EXPORTS = ("l2a_version", "l2a_strerror", "l2a_route_workspace_bytes", "l2a_attn_workspace_bytes",
-           "l2a_kblk_entries", "l2a_route_compact", "l2a_attn_fwd", "l2a_attn_bwd")
+           "l2a_kblk_entries", "l2a_route_compact", "l2a_attn_fwd", "l2a_attn_bwd", "l2a_profile_enable",
+           "l2a_profile_read")
 
 
 class l2a_params(ctypes.Structure):
@@ -128,6 +129,23 @@ def l2a_attn_bwd(p: l2a_params, dO, q_loc, k_loc, v_loc, q_glb, k_glb, v_glb, ro
                             workspace.numel() if workspace is not None else 0, _stream())
     if rc != 0:
         raise L2AError(rc, "l2a_attn_bwd")
+
+
+class l2a_kernel_time(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("ms", ctypes.c_float)]
+
+
+def profile_enable(on: bool) -> None:
+    lib().l2a_profile_enable(1 if on else 0)
+
+
+def profile_read(max_records: int = 4096):
+    """-> [(kernel name, milliseconds)] in launch order since the last read; synchronises."""
+    buf = (l2a_kernel_time * max_records)()
+    L = lib()
+    L.l2a_profile_read.restype = ctypes.c_int
+    n = L.l2a_profile_read(buf, max_records)
+    return [(buf[i].name.decode(), float(buf[i].ms)) for i in range(min(n, max_records))]
 
 
 # ------------------------------------------------------------------------------------------

@@ -453,6 +453,7 @@ int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, c
     const long long rows = (long long)g.T * g.G;
     const int bq = 128 * (nqb == 2 ? 2 : 1);
     const dim3 grid((unsigned)((rows + bq - 1) / bq), g.B * g.Hkv);
+    KernelTimer kt(rs.local ? "bwd_dq_local" : "bwd_dq_global", st);
     if (nqb == 2) {
         if (rs.local)
             hipLaunchKernelGGL((bwd_dq_kernel<2, true>), grid, dim3(kThreads), 0, st, a);
@@ -494,6 +495,7 @@ int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* q, c
         attr_set = true;
     }
     const dim3 grid((g.T + kKeysPerWg - 1) / kKeysPerWg, g.B * g.Hkv);
+    KernelTimer kt("bwd_dkdv", st);
     hipLaunchKernelGGL(bwd_dkdv_kernel, grid, dim3(kThreads), smem, st, a);
     return launch_status();
 }

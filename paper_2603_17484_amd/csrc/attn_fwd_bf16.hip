@@ -267,6 +267,7 @@ int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, cons
     const long long rows = (long long)g.T * g.G;
     const int bq = 128 * (nqb == 1 ? 1 : 2);
     const dim3 grid((unsigned)((rows + bq - 1) / bq), g.B * g.Hkv);
+    KernelTimer kt(rs.local ? "fwd_local" : "fwd_global", st);
     if (nqb == 1) {
         if (rs.local)
             hipLaunchKernelGGL((fwd_kernel<1, true>), grid, dim3(kThreads), 0, st, a);

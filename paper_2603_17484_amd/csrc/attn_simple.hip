@@ -227,6 +227,7 @@ static const T* cp(const void* p) { return (const T*)p; }
 int simple_fwd(const Geom& g, int dtype, const RowSet& rs, const void* q, const void* k, const void* v,
                const FwdOut& out, hipStream_t st) {
     const dim3 grid = row_grid(g);
+    KernelTimer kt(rs.local ? "scalar_fwd_local" : "scalar_fwd_global", st);
     if (dtype == L2A_FP32 && g.D == 64)
         hipLaunchKernelGGL((simple_fwd_kernel<float, 16>), grid, dim3(kThreads), 0, st, g, rs, cp<float>(q), cp<float>(k), cp<float>(v), out);
     else if (dtype == L2A_FP32 && g.D == 128)
@@ -243,6 +244,7 @@ int simple_fwd(const Geom& g, int dtype, const RowSet& rs, const void* q, const 
 int simple_bwd_dq(const Geom& g, int dtype, const RowSet& rs, const void* q, const void* k, const void* v,
                   const void* dO, const float* lse, float* delta, void* dq, int accumulate, hipStream_t st) {
     const dim3 grid = row_grid(g);
+    KernelTimer kt(rs.local ? "scalar_bwd_dq_local" : "scalar_bwd_dq_global", st);
     if (dtype == L2A_FP32 && g.D == 64)
         hipLaunchKernelGGL((simple_bwd_dq_kernel<float, 16>), grid, dim3(kThreads), 0, st, g, rs, cp<float>(q), cp<float>(k), cp<float>(v), cp<float>(dO), lse, delta, (float*)dq, accumulate);
     else if (dtype == L2A_FP32 && g.D == 128)
@@ -267,6 +269,7 @@ int simple_bwd_dkdv(const Geom& g, int dtype, const RowSet* sets, int nsets, con
         s.delta[i] = delta[i];
     }
     const dim3 grid((g.T + kRowsPerBlock - 1) / kRowsPerBlock, g.B * g.Hkv);
+    KernelTimer kt("scalar_bwd_dkdv", st);
     if (dtype == L2A_FP32 && g.D == 64)
         hipLaunchKernelGGL((simple_bwd_dkdv_kernel<float, 16>), grid, dim3(kThreads), 0, st, g, s, cp<float>(q), cp<float>(k), cp<float>(v), cp<float>(dO), (float*)dk, (float*)dv);
     else if (dtype == L2A_FP32 && g.D == 128)

@@ -29,6 +29,16 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? L2A_OK : L2A_ERR_LAUNCH; }
 
+// Optional per-kernel timing (l2a_profile_enable / l2a_profile_read): when enabled, a KernelTimer
+// around a launch records a HIP event on the launch stream before and after it.
+void profile_begin(const char* name, hipStream_t st);
+void profile_end(hipStream_t st);
+struct KernelTimer {
+    hipStream_t st;
+    KernelTimer(const char* name, hipStream_t s) : st(s) { profile_begin(name, s); }
+    ~KernelTimer() { profile_end(st); }
+};
+
 // ---- route_compact.hip
 size_t route_workspace_bytes(const l2a_params& p);
 int route_compact(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, int32_t* count,

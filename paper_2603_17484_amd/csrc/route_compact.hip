@@ -152,8 +152,14 @@ int route_compact(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, in
     a.nkb = (p.T + 63) / 64;
     if (a.G > kMaxG) return L2A_ERR_UNSUPPORTED;
     const dim3 grid(a.nchunks, p.B * p.Hkv);
-    hipLaunchKernelGGL(route_count_kernel, grid, dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(route_write_kernel, grid, dim3(kThreads), 0, st, a);
+    {
+        KernelTimer kt("route_count", st);
+        hipLaunchKernelGGL(route_count_kernel, grid, dim3(kThreads), 0, st, a);
+    }
+    {
+        KernelTimer kt("route_write", st);
+        hipLaunchKernelGGL(route_write_kernel, grid, dim3(kThreads), 0, st, a);
+    }
     return launch_status();
 }
 

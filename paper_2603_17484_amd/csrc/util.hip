@@ -53,6 +53,7 @@ int row_deltas(const Geom& g, int dtype, const void* dO, const void* S, const vo
                float* delta_g, hipStream_t st) {
     const long long nrows = (long long)g.B * g.T * g.Hq;
     const dim3 grid((unsigned)((nrows + kThreads / 16 - 1) / (kThreads / 16)));
+    KernelTimer kt("row_deltas", st);
     if (dtype == L2A_FP32 && g.D == 64)
         hipLaunchKernelGGL((row_deltas_kernel<float, 4>), grid, dim3(kThreads), 0, st, g, (const float*)dO, (const float*)S, (const float*)A, delta_l, delta_g);
     else if (dtype == L2A_FP32 && g.D == 128)
@@ -72,6 +73,7 @@ int fill_zero(void* ptr, size_t bytes, hipStream_t st) {
     if (n == 0) return L2A_OK;
     size_t blocks = (n + kThreads - 1) / kThreads;
     if (blocks > 65536) blocks = 65536;
+    KernelTimer kt("fill", st);
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, (uint32_t*)ptr, n, 0u);
     return launch_status();
 }
@@ -82,6 +84,7 @@ int fill_f32(float* ptr, size_t n, float value, hipStream_t st) {
     if (blocks > 65536) blocks = 65536;
     uint32_t bits;
     __builtin_memcpy(&bits, &value, 4);
+    KernelTimer kt("fill", st);
     hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, (uint32_t*)ptr, n, bits);
     return launch_status();
 }
