@@ -170,6 +170,10 @@ def alloc_fwd(p: l2a_params, device="cuda", branches=True):
     return O, lse_l, lse_g, S, A
 
 
+def alloc_fwd_workspace(p: l2a_params, device="cuda"):
+    return _ws(lib().l2a_attn_workspace_bytes(ctypes.byref(p), 0), device)
+
+
 def alloc_bwd(p: l2a_params, device="cuda"):
     dt = torch_dtype(p)
     dq = torch.empty((p.B, p.T, p.Hq, p.D), dtype=dt, device=device)

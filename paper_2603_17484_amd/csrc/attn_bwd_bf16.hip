@@ -12,6 +12,8 @@
 //                     Local rows that can see the block, then the compacted Global rows from
 //                     kblk_first_row on.  The G heads of a KV group are rows of the same list,
 //                     so the sum over heads needs no second pass.
+#include <type_traits>
+
 #include "mfma.hpp"
 
 namespace l2a {
@@ -245,6 +247,29 @@ struct RowTileLds {
     int pad[kRT];  // keeps the struct a multiple of 16 bytes
 };
 
+// One element of the backward softmax: register r of an S tile (row 8 (r/4) + 4 h + r%4, this
+// lane's key).  s <- P, dp <- dS.
+template <bool MASK>
+__device__ __forceinline__ void bwd_softmax_elem(int r, f32x16& s, f32x16& dp, const f32x4 (&l2)[4],
+                                                 const f32x4 (&dl)[4], const i32x4 (&ps)[4], float c, int key,
+                                                 int T, int W, bool local) {
+    const int rg = r >> 2, e = r & 3;
+    float p = fast_exp2(fmaf(s[r], c, -l2[rg][e]));
+    if (MASK) {
+        const int rp = ps[rg][e];
+        bool ok = rp >= key && key < T;
+        if (local) ok = ok && (rp - key <= W);
+        p = ok ? p : 0.f;
+    }
+    s[r] = p;
+    dp[r] = p * (dp[r] - dl[rg][e]);
+}
+
+// Keeps the instruction scheduler from moving anything across this point: the tile body below
+// is software-pipelined by hand (matrix-core instructions interleaved with the VALU work and
+// the LDS traffic of the neighbouring stages), one wavefront per SIMD.
+#define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     RowTileLds* lds = reinterpret_cast<RowTileLds*>(smem);  // [2]
@@ -270,30 +295,42 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     }
 
     // ---- row ranges of each set that can see this block of keys, as 64-row tiles
-    int r_begin[2] = {0, 0}, r_end[2] = {0, 0}, ntile[2] = {0, 0};
-    for (int s = 0; s < a.nsets; ++s) {
-        const RowSet& rs = a.rs[s];
+    int rb0 = 0, re0 = 0, rb1 = 0, re1 = 0;
+    {
+        const RowSet& rs = a.rs[0];
         if (rs.local) {
-            r_begin[s] = k0 * gm.G;
-            r_end[s] = min(gm.T, k0 + kKeysPerWg + gm.W) * gm.G;
+            rb0 = k0 * gm.G;
+            re0 = min(gm.T, k0 + kKeysPerWg + gm.W) * gm.G;
         } else {
-            r_begin[s] = rs.kblk_first_row ? rs.kblk_first_row[(size_t)bh * (nkb + 1) + (k0 >> 6)] : k0 * gm.G;
-            r_end[s] = rows_total(rs, gm, bh);
+            rb0 = rs.kblk_first_row ? rs.kblk_first_row[(size_t)bh * (nkb + 1) + (k0 >> 6)] : k0 * gm.G;
+            re0 = rows_total(rs, gm, bh);
         }
-        ntile[s] = r_end[s] > r_begin[s] ? (r_end[s] - r_begin[s] + kRT - 1) / kRT : 0;
     }
-    const int total_tiles = ntile[0] + ntile[1];
+    if (a.nsets > 1) {
+        const RowSet& rs = a.rs[1];
+        if (rs.local) {
+            rb1 = k0 * gm.G;
+            re1 = min(gm.T, k0 + kKeysPerWg + gm.W) * gm.G;
+        } else {
+            rb1 = rs.kblk_first_row ? rs.kblk_first_row[(size_t)bh * (nkb + 1) + (k0 >> 6)] : k0 * gm.G;
+            re1 = rows_total(rs, gm, bh);
+        }
+    }
+    const int nt0 = re0 > rb0 ? (re0 - rb0 + kRT - 1) / kRT : 0;
+    const int nt1 = re1 > rb1 ? (re1 - rb1 + kRT - 1) / kRT : 0;
+    const int total_tiles = nt0 + nt1;
 
     const int r4 = (threadIdx.x >> 4) * 4;
+    const int c8 = (threadIdx.x & 15) * 8;
     TileRegs qr, gr;
     float st_lse2 = 0.f, st_delta = 0.f;
     int st_pos = -1;
     // tile `it` of the concatenated list -> registers
     auto load_tile = [&](int it) {
-        const int s = it < ntile[0] ? 0 : 1;
+        const int s = it < nt0 ? 0 : 1;
         const RowSet& rs = a.rs[s];
-        const int rt0 = r_begin[s] + (it - (s ? ntile[0] : 0)) * kRT;
-        const int last = r_end[s] - 1;
+        const int rt0 = (s ? rb1 : rb0) + (it - (s ? nt0 : 0)) * kRT;
+        const int last = (s ? re1 : re0) - 1;
         size_t offs[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -319,18 +356,32 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             }
         }
     };
-    auto store_tile = [&](int buf) {
-        RowTileLds& t = lds[buf];
-        tile_store_rowmajor(qr, t.q_rm);
-        tile_store_transposed(qr, t.q_t);
-        tile_store_rowmajor(gr, t.g_rm);
-        tile_store_transposed(gr, t.g_t);
-        if (threadIdx.x < kRT) {
-            t.lse2[threadIdx.x] = st_lse2;
-            t.delta[threadIdx.x] = st_delta;
-            t.pos[threadIdx.x] = st_pos;
+    // registers -> LDS in 16 pieces, so that the pieces can be spread between matrix-core instructions
+    auto store_piece = [&](RowTileLds& t, auto ic) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i < 4) {
+            *reinterpret_cast<u32x4*>(t.q_rm + (r4 + i) * kRowPad + c8) = qr.x[i];
+        } else if constexpr (i < 8) {
+            *reinterpret_cast<u32x4*>(t.g_rm + (r4 + i - 4) * kRowPad + c8) = gr.x[i - 4];
+        } else {
+            const TileRegs& x = i < 12 ? qr : gr;
+            __bf16* dst = i < 12 ? t.q_t : t.g_t;
+            constexpr int p = i & 3;
+            const uint32_t w0 = x.x[0][p], w1 = x.x[1][p], w2 = x.x[2][p], w3 = x.x[3][p];
+            u32x2 even = {(w0 & 0xffffu) | (w1 << 16), (w2 & 0xffffu) | (w3 << 16)};
+            u32x2 odd = {(w0 >> 16) | (w1 & 0xffff0000u), (w2 >> 16) | (w3 & 0xffff0000u)};
+            *reinterpret_cast<u32x2*>(dst + (c8 + 2 * p) * kColPad + r4) = even;
+            *reinterpret_cast<u32x2*>(dst + (c8 + 2 * p + 1) * kColPad + r4) = odd;
+        }
+        if constexpr (i == 0) {
+            if (threadIdx.x < kRT) {
+                t.lse2[threadIdx.x] = st_lse2;
+                t.delta[threadIdx.x] = st_delta;
+                t.pos[threadIdx.x] = st_pos;
+            }
         }
     };
+    auto store_all = [&](RowTileLds& t) { static_for<0, 16>([&](auto ic) { store_piece(t, ic); }); };
 
     f32x16 dkacc[4], dvacc[4];
 #pragma unroll
@@ -341,86 +392,174 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             dvacc[d][r] = 0.f;
         }
 
+    // One 64-row tile against this wavefront's 32 keys: 64 matrix-core instructions, issued as 64
+    // slots.  Slot m issues instruction m, the LDS read of the operand of instruction m + kAhead,
+    // and a share of the VALU / LDS-store work of the neighbouring stages:
+    //   slots  0-15  S0, dP0 (rows 0-31)
+    //   slots 16-31  S1, dP1 (rows 32-63)   | softmax-backward of rows 0-31
+    //   slots 32-47  dV, dK from rows 0-31  | softmax-backward of rows 32-63
+    //   slots 48-63  dV, dK from rows 32-63 | next tile: registers -> LDS
+    // Only the operands of the next kAhead slots are live, so the register file also holds the
+    // wavefront's K/V operands and the 128 accumulator registers.
+    auto tile_body = [&](auto mask_tag, const RowTileLds& t, bool local, bool do_store, RowTileLds& tn) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        constexpr int kAhead = 4;
+        const float c = gm.scale_log2;
+        bf16x8 opnd[64 + kAhead];
+        f32x4 l2a[4], dla[4], l2b[4], dlb[4];
+        i32x4 psa[4], psb[4];
+        f32x16 s0, dp0, s1, dp1;
+        bf16x8 pT[4], dsT[4];
+        // operand of instruction m, read from LDS
+        auto read_operand = [&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            if constexpr (m < 64) {
+                constexpr int i = m & 15, ks = i >> 1;
+                if constexpr (m < 32) {
+                    const int row = (m < 16 ? 0 : 32) + n;
+                    if constexpr (i & 1) opnd[m] = lds_rowmajor(t.g_rm, row, ks, h);
+                    else opnd[m] = lds_rowmajor(t.q_rm, row, ks, h);
+                } else {
+                    constexpr int step = (m - 32) >> 3, d = (i >> 1) & 3;
+                    if constexpr (i & 1) opnd[m] = lds_transposed(t.q_t, d * 32 + n, step, h);
+                    else opnd[m] = lds_transposed(t.g_t, d * 32 + n, step, h);
+                }
+            }
+        };
+        auto issue = [&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            constexpr int i = m & 15, ks = i >> 1, d = (i >> 1) & 3;
+            if constexpr (m < 16) {
+                if constexpr (i & 1) dp0 = mfma32(opnd[m], vreg[ks], dp0);
+                else s0 = mfma32(opnd[m], kreg[ks], s0);
+            } else if constexpr (m < 32) {
+                if constexpr (i & 1) dp1 = mfma32(opnd[m], vreg[ks], dp1);
+                else s1 = mfma32(opnd[m], kreg[ks], s1);
+            } else {
+                constexpr int step = (m - 32) >> 3;
+                if constexpr (i & 1) dkacc[d] = mfma32(dsT[step], opnd[m], dkacc[d]);
+                else dvacc[d] = mfma32(pT[step], opnd[m], dvacc[d]);
+            }
+        };
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            s0[r] = 0.f;
+            dp0[r] = 0.f;
+            s1[r] = 0.f;
+            dp1[r] = 0.f;
+        }
+        static_for<0, kAhead>([&](auto mc) { read_operand(mc); });
+        L2A_FENCE();
+        static_for<0, 64>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            issue(mc);
+            read_operand(std::integral_constant<int, m + kAhead>{});
+            if constexpr (m >= 8 && m < 12) {  // per-row statistics of rows 0-31
+                constexpr int rg = m - 8;
+                l2a[rg] = *reinterpret_cast<const f32x4*>(&t.lse2[8 * rg + 4 * h]);
+                dla[rg] = *reinterpret_cast<const f32x4*>(&t.delta[8 * rg + 4 * h]);
+                if (MASK) psa[rg] = *reinterpret_cast<const i32x4*>(&t.pos[8 * rg + 4 * h]);
+            }
+            if constexpr (m >= 26 && m < 30) {  // ... of rows 32-63
+                constexpr int rg = m - 26;
+                l2b[rg] = *reinterpret_cast<const f32x4*>(&t.lse2[32 + 8 * rg + 4 * h]);
+                dlb[rg] = *reinterpret_cast<const f32x4*>(&t.delta[32 + 8 * rg + 4 * h]);
+                if (MASK) psb[rg] = *reinterpret_cast<const i32x4*>(&t.pos[32 + 8 * rg + 4 * h]);
+            }
+            if constexpr (m >= 16 && m < 32) {
+                bwd_softmax_elem<MASK>(m - 16, s0, dp0, l2a, dla, psa, c, key, gm.T, gm.W, local);
+                if constexpr (m == 31) {
+                    pT[0] = pack8(s0, 0);
+                    pT[1] = pack8(s0, 1);
+                    dsT[0] = pack8(dp0, 0);
+                    dsT[1] = pack8(dp0, 1);
+                }
+            } else if constexpr (m >= 32 && m < 48) {
+                bwd_softmax_elem<MASK>(m - 32, s1, dp1, l2b, dlb, psb, c, key, gm.T, gm.W, local);
+                if constexpr (m == 47) {
+                    pT[2] = pack8(s1, 0);
+                    pT[3] = pack8(s1, 1);
+                    dsT[2] = pack8(dp1, 0);
+                    dsT[3] = pack8(dp1, 1);
+                }
+            } else if constexpr (m >= 48) {
+                if (do_store) store_piece(tn, std::integral_constant<int, m - 48>{});
+            }
+            L2A_FENCE();
+        });
+    };
+
     if (total_tiles > 0) {
         load_tile(0);
-        store_tile(0);
+        store_all(lds[0]);
     }
     __syncthreads();
 
-    for (int it = 0; it < total_tiles; ++it) {
-        const int cur = it & 1;
-        if (it + 1 < total_tiles) load_tile(it + 1);
-
-        const int s_ = it < ntile[0] ? 0 : 1;
-        const bool local = a.rs[s_].local != 0;
-        const RowTileLds& t = lds[cur];
-
-        // rows of a tile ascend in position: cheap bounds for skipping and for the mask
-        const int rt0 = r_begin[s_] + (it - (s_ ? ntile[0] : 0)) * kRT;
-        const int rt1 = min(rt0 + kRT, r_end[s_]);
-        const int t_pmin = row_code(a.rs[s_], gm, bh, rt0) / gm.G;
-        const int t_pmax = row_code(a.rs[s_], gm, bh, rt1 - 1) / gm.G;
-        bool skip = t_pmax < kw0 || kw0 >= gm.T;
-        if (local) skip = skip || (t_pmin - gm.W > kw0 + 31);
-        if (!skip) {
-            bool need_mask = (t_pmin < kw0 + 31) || (rt1 - rt0 < kRT) || (kw0 + 31 >= gm.T);
-            if (local) need_mask = need_mask || (t_pmax - gm.W > kw0);
-
-            bf16x8 pT[4], dsT[4];
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                // S = Q K^T and dP = dO V^T for 32 rows x this wavefront's 32 keys
-                f32x16 s, dp;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    s[r] = 0.f;
-                    dp[r] = 0.f;
-                }
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 aq = lds_rowmajor(t.q_rm, qb * 32 + n, ks, h);
-                    const bf16x8 ag = lds_rowmajor(t.g_rm, qb * 32 + n, ks, h);
-                    s = mfma32(aq, kreg[ks], s);
-                    dp = mfma32(ag, vreg[ks], dp);
-                }
-#pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    const int row0 = qb * 32 + 8 * rg + 4 * h;  // registers 4 rg .. 4 rg + 3 hold rows row0 .. row0 + 3
-                    const f32x4 l2 = *reinterpret_cast<const f32x4*>(&t.lse2[row0]);
-                    const f32x4 dl = *reinterpret_cast<const f32x4*>(&t.delta[row0]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int r = 4 * rg + e;
-                        float p = fast_exp2(fmaf(s[r], gm.scale_log2, -l2[e]));
-                        if (need_mask) {
-                            const int rp = t.pos[row0 + e];
-                            bool ok = rp >= key && key < gm.T;
-                            if (local) ok = ok && (rp - key <= gm.W);
-                            p = ok ? p : 0.f;
-                        }
-                        s[r] = p;
-                        dp[r] = p * (dp[r] - dl[e]);
-                    }
-                }
-                pT[qb * 2 + 0] = pack8(s, 0);
-                pT[qb * 2 + 1] = pack8(s, 1);
-                dsT[qb * 2 + 0] = pack8(dp, 0);
-                dsT[qb * 2 + 1] = pack8(dp, 1);
-            }
-            // dV += P^T dO,  dK += dS^T Q   (contract over the tile's 64 rows)
-#pragma unroll
-            for (int step = 0; step < 4; ++step)
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const bf16x8 bg = lds_transposed(t.g_t, d * 32 + n, step, h);
-                    const bf16x8 bq = lds_transposed(t.q_t, d * 32 + n, step, h);
-                    dvacc[d] = mfma32(pT[step], bg, dvacc[d]);
-                    dkacc[d] = mfma32(dsT[step], bq, dkacc[d]);
-                }
+    // The tiles of a set form three runs: a head whose rows can lie before some key of the block
+    // (causal mask), a middle that needs no mask at all, and a tail (sliding-window edge, ragged
+    // last tile).  Each run gets its own loop so the common case is straight-line code.
+    auto split = [&](const RowSet& rs, int rb, int re, int nt, int& head, int& tail_start) {
+        if (nt == 0) {
+            head = 0;
+            tail_start = 0;
+            return;
         }
+        const int kend = k0 + kKeysPerWg;  // rows at positions >= kend see every key of the block
+        int r_mid;
+        if (kend > gm.T)
+            r_mid = re;
+        else if (rs.local || !rs.kblk_first_row)
+            r_mid = kend * gm.G;
+        else
+            r_mid = rs.kblk_first_row[(size_t)bh * (nkb + 1) + (kend >> 6)];
+        head = min(nt, max(0, (r_mid - rb + kRT - 1) / kRT));
+        tail_start = ((re - rb) % kRT) ? nt - 1 : nt;
+        if (rs.local) {
+            const long long r_suf = (long long)(k0 + gm.W + 1) * gm.G;  // first row whose window starts after k0
+            if (r_suf < re) tail_start = min(tail_start, (int)((r_suf - rb) / kRT));
+        }
+        tail_start = max(tail_start, head);
+    };
+    int head0, tail0, head1, tail1;
+    split(a.rs[0], rb0, re0, nt0, head0, tail0);
+    split(a.rs[1], rb1, re1, nt1, head1, tail1);
 
-        if (it + 1 < total_tiles) store_tile(cur ^ 1);
-        __syncthreads();
+    for (int seg = 0; seg < 6; ++seg) {
+        const int set = seg / 3, part = seg - 3 * set;
+        const int base = set ? nt0 : 0;
+        const int hd = set ? head1 : head0, tl = set ? tail1 : tail0, nt = set ? nt1 : nt0;
+        const int it_begin = base + (part == 0 ? 0 : (part == 1 ? hd : tl));
+        const int it_end = base + (part == 0 ? hd : (part == 1 ? tl : nt));
+        if (it_begin >= it_end) continue;
+        const RowSet& rs = a.rs[set];
+        const bool local = rs.local != 0;
+        const int rbs = set ? rb1 : rb0, res = set ? re1 : re0;
+        if (part == 1) {
+            for (int it = it_begin; it < it_end; ++it) {
+                const int cur = it & 1;
+                const bool more = it + 1 < total_tiles;
+                if (more) load_tile(it + 1);
+                if (kw0 < gm.T) tile_body(std::false_type{}, lds[cur], local, more, lds[cur ^ 1]);
+                else if (more) store_all(lds[cur ^ 1]);
+                __syncthreads();
+            }
+        } else {
+            for (int it = it_begin; it < it_end; ++it) {
+                const int cur = it & 1;
+                const bool more = it + 1 < total_tiles;
+                if (more) load_tile(it + 1);
+                // rows of a tile ascend in position: cheap per-wavefront bounds for skipping
+                const int rt0 = rbs + (it - base) * kRT;
+                const int rt1 = min(rt0 + kRT, res);
+                const int t_pmin = row_code(rs, gm, bh, rt0) / gm.G;
+                const int t_pmax = row_code(rs, gm, bh, rt1 - 1) / gm.G;
+                bool skip = t_pmax < kw0 || kw0 >= gm.T;
+                if (local) skip = skip || (t_pmin - gm.W > kw0 + 31);
+                if (!skip) tile_body(std::true_type{}, lds[cur], local, more, lds[cur ^ 1]);
+                else if (more) store_all(lds[cur ^ 1]);
+                __syncthreads();
+            }
+        }
     }
 
     // ---- write dK, dV: lane = channel d*32+n, register r = key c_row(r, h)

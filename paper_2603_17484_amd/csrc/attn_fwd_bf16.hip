@@ -6,37 +6,334 @@
 // The epilogue writes the log-sum-exp and merges into O (Sec. 3.1 Eq. 5), so the scatter of
 // Alg. 1's last step costs no extra pass.
 //
-// Work decomposition.  One workgroup = 4 wavefronts = a tile of 4 * 32 * NQB consecutive rows
-// of one (batch, KV head); rows of the G query heads of the group are interleaved, so every
-// row of a tile reads the same K/V.  K/V are streamed through LDS in blocks of 64 keys
-// (double buffered, one barrier per block); V is transposed on its way into LDS.
+// Work decomposition.  One workgroup = 4 wavefronts = a tile of 256 consecutive rows of one
+// (batch, KV head); the rows of the G query heads of the group are interleaved, so every row of
+// a tile reads the same K/V.  K and the token-minor copy of V are streamed through LDS in blocks
+// of 64 keys by direct global->LDS loads (two buffers each, one barrier per block).
 //
 // Everything is computed transposed so that a lane owns a query row:
-//   S^T[key, row]  = K Q^T     A = K tile (LDS, row-major), B = Q (registers, loaded once)
-//   O^T[ch,  row] += V^T P^T   A = V tile (LDS, transposed), B = P^T = the S^T accumulators
-// A lane then holds 32 scores of one row per K block (the lane 32 apart holds the other 32):
-// row max / row sum are in-register reductions plus one cross-lane exchange, and the
-// rescaling of O is a per-lane scalar.
-#include "mfma.hpp"
+//   S^T[key, row]  = K Q^T     A = K block (LDS), B = Q (registers, loaded once)
+//   O^T[ch,  row] += V^T P^T   A = V block (LDS, token-minor), B = P^T = the S^T accumulators
+// A lane holds 32 scores of one row per block (the lane 32 apart holds the other 32): row max
+// and row sum are in-register reductions plus one cross-lane exchange, and rescaling O is a
+// per-lane scalar.
+//
+// Software pipeline (one wavefront per SIMD, 64 matrix-core instructions per block, issued as 64
+// slots): while block j's scores go through the softmax on the VALU, the matrix cores first
+// compute block j+1's scores (slots 0-31) and then accumulate P_j V_j (slots 32-63, in the
+// order the softmax finishes the 16-key groups).  LDS operand reads run a few slots ahead.
+#include "tiles.hpp"
 
 namespace l2a {
 namespace {
 
-constexpr int kBK = 64;  // keys per LDS block
+constexpr int kBK = 64;  // keys per block
+constexpr int kNQB = 2;  // 32-row blocks per wavefront
+constexpr int kRW = 32 * kNQB;
+constexpr int kBQ = 4 * kRW;
+constexpr int kAhead = 2;  // operand look-ahead, in operands (each feeds two instructions)
+
+#define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 struct FwdArgs {
     Geom gm;
     RowSet rs;
     const __bf16* q;
     const __bf16* k;
-    const __bf16* v;
+    const __bf16* v;   // V as given (fix-up kernel only)
+    const __bf16* vt;  // token-minor copy of V: [B*Hkv][128][vt_cap]
+    int vt_cap;
+    int32_t* redo;  // [B*Hkv][gridDim.x]: set to 1 for a tile whose rows must be recomputed by the fix-up kernel
     FwdOut out;
 };
 
-template <int NQB, bool LOCAL>
+struct Scores {
+    f32x16 s[kNQB];  // 32 keys x (kNQB x 32) rows
+};
+
+template <int V>
+using Int = std::integral_constant<int, V>;
+
+template <bool LOCAL>
 __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
-    constexpr int RW = 32 * NQB;  // rows per wavefront
-    constexpr int BQ = 4 * RW;    // rows per workgroup
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_v[2][kD * kBK];
+
+    const Geom& gm = a.gm;
+    const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
+    const int n_rows = rows_total(a.rs, gm, bh);
+    const int n_tiles = (n_rows + kBQ - 1) / kBQ;
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int tile = n_tiles - 1 - (int)blockIdx.x;  // longest prefixes first
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, h = lane >> 5;
+
+    // ---- rows of this workgroup / wavefront / lane
+    const int wg_r0 = tile * kBQ;
+    const int wg_r1 = min(wg_r0 + kBQ, n_rows);  // exclusive
+    const int wg_pmin = row_code(a.rs, gm, bh, wg_r0) / gm.G;
+    const int wg_pmax = row_code(a.rs, gm, bh, wg_r1 - 1) / gm.G;
+    const int wv_r0 = wg_r0 + wave * kRW;
+    const bool wave_active = wv_r0 < n_rows;
+
+    int pos[kNQB], head[kNQB];
+    bool valid[kNQB];
+    bf16x8 qreg[kNQB][8];
+#pragma unroll
+    for (int c = 0; c < kNQB; ++c) {
+        const int r = wv_r0 + c * 32 + n;
+        valid[c] = r < n_rows;
+        // rows past the end repeat the last row: computed, never written
+        const int code = row_code(a.rs, gm, bh, min(r, n_rows - 1));
+        pos[c] = code / gm.G;
+        head[c] = hk * gm.G + (code - pos[c] * gm.G);
+        const __bf16* qp = a.q + (((size_t)b * gm.T + pos[c]) * gm.Hq + head[c]) * kD + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qreg[c][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    }
+
+    // ---- block range of the workgroup, and its three runs: blocks that need the window-start
+    // mask (LOCAL only), blocks no row of the tile needs a mask for, blocks on the causal diagonal
+    const int jb0 = LOCAL ? max(wg_pmin - gm.W, 0) / kBK : 0;
+    const int jb1 = wg_pmax / kBK;  // inclusive
+    int j_mid = jb0;                // first block without window-start masking
+    if (LOCAL) j_mid = min(jb1 + 1, max(jb0, (max(wg_pmax - gm.W, 0) + kBK - 1) / kBK));
+    const int j_diag = max(j_mid, min(jb1 + 1, (wg_pmin + 1) / kBK));  // first block with a key > some row
+
+    const size_t kv_row = (size_t)gm.Hkv * kD;
+    const __bf16* kbase = a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
+    const __bf16* vtbase = a.vt + (size_t)bh * kD * a.vt_cap;
+    const unsigned lds_k0 = lds_offset(&lds_k[0][0]), lds_v0 = lds_offset(&lds_v[0][0]);
+    auto load_k = [&](int jb, int buf) __attribute__((always_inline)) {
+        // keys past the end of the sequence are clamped: always masked, never out of bounds
+        dma_rm_tile<kBK>(lds_k0 + buf * (kBK * 256),
+                         [&](int r) { return kbase + (size_t)min(jb * kBK + r, gm.T - 1) * kv_row; });
+    };
+    auto load_v = [&](int jb, int buf) __attribute__((always_inline)) {
+        dma_tm_tile<kBK>(lds_v0 + buf * (kD * kBK * 2), vtbase + (size_t)jb * kBK, (size_t)a.vt_cap);
+    };
+
+    f32x16 oacc[4][kNQB];
+    float mref[kNQB], negm[kNQB], l[kNQB];
+#pragma unroll
+    for (int c = 0; c < kNQB; ++c) {
+        l[c] = 0.f;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[d][c][r] = 0.f;
+    }
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto key_ok = [&](int key, int c) __attribute__((always_inline)) {
+        bool ok = key <= pos[c];
+        if (LOCAL) ok = ok && (key >= pos[c] - gm.W);
+        return ok;
+    };
+
+    // One half-block (32 keys, half KB of block jb; keys k0 .. k0+31): exp of `cur` against the
+    // row's fixed reference, overlapped with the scores of the next half-block into `nxt` (K rows
+    // krow0.. of tile kt) and with O += P V for this half-block (tile vt).  32 matrix-core
+    // instructions = 32 slots:
+    //   slots  0-15  next half-block's scores | exp, row sum, pack P  (pair q in slot 3 q / 2)
+    //   slots 16-31  O += P V
+    auto half_block = [&](auto mask_tag, auto kb_tag, Scores& cur, Scores& nxt, const __bf16* kt, int krow0,
+                          const __bf16* vt, int k0) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        constexpr int KB = decltype(kb_tag)::value;
+        const float c2 = gm.scale_log2;
+        bf16x8 opnd[16 + kAhead];
+        uint32_t pw[kNQB][2][4];  // P as packed bf16 pairs: [row block][16-key group][dword]
+        float rsum[kNQB];
+#pragma unroll
+        for (int c = 0; c < kNQB; ++c) rsum[c] = 0.f;
+        // operand o: o < 8 -> K rows of the next half-block (ks = o); else V^T (16-key group, channel block)
+        auto read_operand = [&](auto oc) {
+            constexpr int o = decltype(oc)::value;
+            if constexpr (o < 8) opnd[o] = rm_operand(kt, krow0 + n, o, h);
+            else if constexpr (o < 16) opnd[o] = tm_operand<kBK>(vt, ((o - 8) & 3) * 32 + n, 2 * KB + ((o - 8) >> 2), h);
+        };
+        auto issue = [&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            if constexpr (mm < 16) {
+                constexpr int ks = mm >> 1, c = mm & 1;
+                nxt.s[c] = mfma32(opnd[ks], qreg[c][ks], ks == 0 ? zero16 : nxt.s[c]);
+            } else {
+                constexpr int x = mm - 16, grp = x >> 3, d = (x >> 1) & 3, c = x & 1;
+                const u32x4 pv = {pw[c][grp][0], pw[c][grp][1], pw[c][grp][2], pw[c][grp][3]};
+                oacc[d][c] = mfma32(opnd[8 + (x >> 1)], __builtin_bit_cast(bf16x8, pv), oacc[d][c]);
+            }
+        };
+        // exp of one pair of scores: pair q in 0..15, in the order the P V product consumes them
+        auto exp_pair = [&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            constexpr int grp = q >> 3, c = (q >> 2) & 1, i2 = (q & 3) * 2, r = grp * 8 + i2;
+            float p0 = fast_exp2(fmaf(cur.s[c][r], c2, negm[c]));
+            float p1 = fast_exp2(fmaf(cur.s[c][r + 1], c2, negm[c]));
+            if (MASK) {
+                p0 = key_ok(k0 + c_row(r, h), c) ? p0 : 0.f;
+                p1 = key_ok(k0 + c_row(r + 1, h), c) ? p1 : 0.f;
+            }
+            rsum[c] += p0 + p1;
+            f32x2 f = {p0, p1};
+            pw[c][grp][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+        };
+
+        static_for<0, kAhead>([&](auto oc) { read_operand(oc); });
+        L2A_FENCE();
+        static_for<0, 32>([&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            issue(mc);
+            if constexpr ((mm & 1) == 0) read_operand(Int<(mm >> 1) + kAhead>{});
+            static_for<0, 16>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                if constexpr ((3 * q) / 2 == mm) exp_pair(qc);
+            });
+            L2A_FENCE();
+        });
+#pragma unroll
+        for (int c = 0; c < kNQB; ++c) l[c] += rsum[c];
+    };
+
+    // ---- prologue: K of the first two blocks, V of the first
+    Scores Sa, Sb;
+    load_k(jb0, 0);
+    if (jb0 < jb1) load_k(jb0 + 1, 1);
+    load_v(jb0, 0);
+    dma_wait();
+    __syncthreads();
+    // Reference of every row's exponentials: the largest score among the row's keys in the first
+    // two blocks (every row of the tile has a key there).  It is never updated: scores that come
+    // later may exceed it, which costs no accuracy in floating point; the epilogue checks that the
+    // row sums stayed far from overflow and otherwise leaves the tile to the fix-up kernel.
+    if (wave_active) {
+#pragma unroll
+        for (int c = 0; c < kNQB; ++c) mref[c] = -INFINITY;
+        const int nb = jb0 < jb1 ? 2 : 1;
+        for (int bi = 0; bi < nb; ++bi) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                Scores S;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const bf16x8 op = rm_operand(&lds_k[bi][0], kb * 32 + n, ks, h);
+#pragma unroll
+                    for (int c = 0; c < kNQB; ++c) S.s[c] = mfma32(op, qreg[c][ks], ks == 0 ? zero16 : S.s[c]);
+                }
+#pragma unroll
+                for (int c = 0; c < kNQB; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = (jb0 + bi) * kBK + kb * 32 + c_row(r, h);
+                        mref[c] = fmaxf(mref[c], key_ok(key, c) ? S.s[c][r] : -INFINITY);
+                    }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < kNQB; ++c) {
+            mref[c] = fmaxf(mref[c], __shfl_xor(mref[c], 32)) * gm.scale_log2;
+            if (!(mref[c] > -INFINITY)) mref[c] = 0.f;  // no key in reach yet: any finite reference will do
+            negm[c] = -mref[c];
+        }
+        // scores of the first half-block
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 op = rm_operand(&lds_k[0][0], n, ks, h);
+#pragma unroll
+            for (int c = 0; c < kNQB; ++c) Sa.s[c] = mfma32(op, qreg[c][ks], ks == 0 ? zero16 : Sa.s[c]);
+        }
+    }
+
+    // One block = two half-blocks; Sa holds the scores of a block's first half on entry and exit.
+    auto run = [&](auto mask_tag, int j_begin, int j_end) __attribute__((always_inline)) {
+        for (int jb = j_begin; jb < j_end; ++jb) {
+            const int rel = jb - jb0;
+            const int kbuf = rel % 3, kbuf1 = (rel + 1) % 3, kbuf2 = (rel + 2) % 3;
+            // prefetch: K of block jb+2 (its buffer held block jb-1), V of block jb+1 (held block jb-1)
+            if (jb + 2 <= jb1) load_k(jb + 2, kbuf2);
+            if (jb + 1 <= jb1) load_v(jb + 1, (rel + 1) & 1);
+            if (wave_active) {
+                const __bf16* vt = &lds_v[rel & 1][0];
+                half_block(mask_tag, Int<0>{}, Sa, Sb, &lds_k[kbuf][0], 32, vt, jb * kBK);
+                half_block(mask_tag, Int<1>{}, Sb, Sa, &lds_k[kbuf1][0], 0, vt, jb * kBK + 32);
+            }
+            dma_wait();
+            __syncthreads();
+        }
+    };
+    // three runs: window-start masks (LOCAL), no masks, causal diagonal
+    for (int seg = 0; seg < 3; ++seg) {
+        const int j_begin = seg == 0 ? jb0 : (seg == 1 ? j_mid : j_diag);
+        const int j_end = seg == 0 ? j_mid : (seg == 1 ? j_diag : jb1 + 1);
+        if (seg == 1)
+            run(std::false_type{}, j_begin, j_end);
+        else
+            run(std::true_type{}, j_begin, j_end);
+    }
+
+    // ---- did every row sum stay in range?  (workgroup-wide vote; LDS is free after the last barrier)
+    float lt[kNQB];
+    bool bad = false;
+#pragma unroll
+    for (int c = 0; c < kNQB; ++c) {
+        lt[c] = l[c] + __shfl_xor(l[c], 32);
+        bad = bad || (wave_active && valid[c] && !(lt[c] > 0.f && lt[c] < 1.0e30f));
+    }
+    int* vote = reinterpret_cast<int*>(&lds_v[0][0]);
+    if (threadIdx.x == 0) *vote = 0;
+    __syncthreads();
+    if (bad) *vote = 1;
+    __syncthreads();
+    if (*vote) {
+        if (threadIdx.x == 0) a.redo[(size_t)bh * gridDim.x + tile] = 1;
+        return;
+    }
+
+    // ---- epilogue: normalise, log-sum-exp, merge / scatter
+    if (!wave_active) return;
+    __bf16* mo = (__bf16*)a.out.main_out;
+    __bf16* co = (__bf16*)a.out.copy_out;
+    __bf16* zf = (__bf16*)a.out.zero_fill;
+#pragma unroll
+    for (int c = 0; c < kNQB; ++c) {
+        if (!valid[c]) continue;
+        const float inv = 1.f / lt[c];
+        const size_t base = (((size_t)b * gm.T + pos[c]) * gm.Hq + head[c]) * kD + 4 * h;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const size_t off = base + d * 32 + 8 * rg;
+                f32x4 x = {oacc[d][c][4 * rg + 0] * inv, oacc[d][c][4 * rg + 1] * inv,
+                           oacc[d][c][4 * rg + 2] * inv, oacc[d][c][4 * rg + 3] * inv};
+                if (co) *reinterpret_cast<bf16x4*>(co + off) = __builtin_convertvector(x, bf16x4);
+                if (a.out.merge) {
+                    const bf16x4 old = *reinterpret_cast<const bf16x4*>(mo + off);
+                    x += __builtin_convertvector(old, f32x4);
+                }
+                *reinterpret_cast<bf16x4*>(mo + off) = __builtin_convertvector(x, bf16x4);
+                if (zf) {
+                    const u32x2 z = {0u, 0u};
+                    *reinterpret_cast<u32x2*>(zf + off) = z;
+                }
+            }
+        if (h == 0) {
+            const size_t so = ((size_t)b * gm.Hq + head[c]) * gm.T + pos[c];
+            a.out.lse_out[so] = (mref[c] + __builtin_amdgcn_logf(lt[c])) * kLn2;
+            if (a.out.lse_fill) a.out.lse_fill[so] = -INFINITY;
+        }
+    }
+}
+
+// Fix-up kernel: recomputes the tiles the pipelined kernel gave up on (a later score exceeded a
+// row's fixed reference by so much that a row sum left the safe range).  Same tiling, classical
+// streaming softmax with a running maximum and rescaling (App. C Alg. 1 as printed, with the
+// rescaling factor read as exp(m_old - m_new)); V is transposed on its way into LDS.
+template <bool LOCAL>
+__global__ __launch_bounds__(kThreads) void fwd_fixup_kernel(FwdArgs a) {
+    constexpr int NQB = kNQB;
+    constexpr int RW = 32 * NQB;
+    constexpr int BQ = 4 * RW;
     __shared__ __attribute__((aligned(16))) __bf16 lds_k[2][kTileRows * kRowPad];
     __shared__ __attribute__((aligned(16))) __bf16 lds_v[2][kD * kColPad];
 
@@ -45,7 +342,8 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     const int n_rows = rows_total(a.rs, gm, bh);
     const int n_tiles = (n_rows + BQ - 1) / BQ;
     if ((int)blockIdx.x >= n_tiles) return;
-    const int tile = n_tiles - 1 - (int)blockIdx.x;  // longest prefixes first
+    const int tile = n_tiles - 1 - (int)blockIdx.x;
+    if (!a.redo[(size_t)bh * gridDim.x + tile]) return;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, h = lane >> 5;
@@ -252,34 +550,38 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     }
 }
 
-int env_int(const char* name, int dflt) {
-    const char* s = getenv(name);
-    return s ? atoi(s) : dflt;
-}
 
 }  // namespace
 
-int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const FwdOut& out,
-             hipStream_t st) {
+int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* vt,
+             int vt_cap, int32_t* redo, const FwdOut& out, hipStream_t st) {
     if (g.D != kD) return L2A_ERR_UNSUPPORTED;
-    static const int nqb = env_int("L2A_FWD_NQB", 2);
-    FwdArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, out};
+    FwdArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)vt, vt_cap, redo, out};
     const long long rows = (long long)g.T * g.G;
-    const int bq = 128 * (nqb == 1 ? 1 : 2);
-    const dim3 grid((unsigned)((rows + bq - 1) / bq), g.B * g.Hkv);
-    KernelTimer kt(rs.local ? "fwd_local" : "fwd_global", st);
-    if (nqb == 1) {
+    const dim3 grid((unsigned)((rows + kBQ - 1) / kBQ), g.B * g.Hkv);
+    int r = fill_zero(redo, sizeof(int32_t) * grid.x * grid.y, st);
+    if (r != L2A_OK) return r;
+    {
+        KernelTimer kt(rs.local ? "fwd_local" : "fwd_global", st);
         if (rs.local)
-            hipLaunchKernelGGL((fwd_kernel<1, true>), grid, dim3(kThreads), 0, st, a);
+            hipLaunchKernelGGL((fwd_kernel<true>), grid, dim3(kThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((fwd_kernel<1, false>), grid, dim3(kThreads), 0, st, a);
-    } else {
+            hipLaunchKernelGGL((fwd_kernel<false>), grid, dim3(kThreads), 0, st, a);
+    }
+    {
+        KernelTimer kt(rs.local ? "fwd_local_fixup" : "fwd_global_fixup", st);
         if (rs.local)
-            hipLaunchKernelGGL((fwd_kernel<2, true>), grid, dim3(kThreads), 0, st, a);
+            hipLaunchKernelGGL((fwd_fixup_kernel<true>), grid, dim3(kThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((fwd_kernel<2, false>), grid, dim3(kThreads), 0, st, a);
+            hipLaunchKernelGGL((fwd_fixup_kernel<false>), grid, dim3(kThreads), 0, st, a);
     }
     return launch_status();
+}
+
+// number of redo flags mfma_fwd needs
+size_t mfma_fwd_redo_entries(const Geom& g) {
+    const long long rows = (long long)g.T * g.G;
+    return (size_t)((rows + kBQ - 1) / kBQ) * g.B * g.Hkv;
 }
 
 }  // namespace l2a

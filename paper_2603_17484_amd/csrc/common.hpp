@@ -76,8 +76,17 @@ int fill_zero(void* ptr, size_t bytes, hipStream_t st);
 int fill_f32(float* ptr, size_t n, float value, hipStream_t st);
 
 // ---- attn_fwd_bf16.hip / attn_bwd_bf16.hip : MFMA kernels (bf16, D = 128)
-int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const FwdOut& out,
-             hipStream_t st);
+// vt: token-minor copy of v from pack_kv, [B*Hkv][128][vt_cap]
+// redo: mfma_fwd_redo_entries(g) int32 of scratch
+int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* vt,
+             int vt_cap, int32_t* redo, const FwdOut& out, hipStream_t st);
+size_t mfma_fwd_redo_entries(const Geom& g);
+
+// ---- pack.hip : layout pre-passes (token-minor copies for the matrix-core kernels)
+int pack_kv(const Geom& g, const void* x, void* xt, int cap, hipStream_t st);
+int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, const float* lse, const float* delta,
+              void* qc, void* gc, void* qt, void* gt, float* lse2_c, float* delta_c, int32_t* pos_c, int cap,
+              hipStream_t st);
 int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,
                 const float* lse, float* delta, void* dq, int accumulate, hipStream_t st);
 int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* q, const void* k, const void* v,

@@ -40,10 +40,16 @@ size_t elem_bytes(const l2a_params& p) { return p.dtype == L2A_BF16 ? 2 : 4; }
 size_t q_elems(const l2a_params& p) { return (size_t)p.B * p.T * p.Hq * p.D; }
 size_t stat_elems(const l2a_params& p) { return (size_t)p.B * p.Hq * p.T; }
 
-int fwd_branch(const l2a_params& p, const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v,
-               const FwdOut& out, hipStream_t st) {
-    return use_mfma(p) ? mfma_fwd(g, rs, q, k, v, out, st) : simple_fwd(g, p.dtype, rs, q, k, v, out, st);
+// rows per (b, KV head) of a token-minor copy of K or V
+int kv_cap(const l2a_params& p) { return (p.T + 63) / 64 * 64; }
+size_t kv_copy_bytes(const l2a_params& p) { return (size_t)p.B * p.Hkv * p.D * kv_cap(p) * 2; }
+
+size_t redo_bytes(const l2a_params& p) {
+    const size_t n = mfma_fwd_redo_entries(make_geom(p)) * sizeof(int32_t);
+    return (n + 255) / 256 * 256;
 }
+// two token-minor copies of V (one per branch) and the forward kernels' redo flags
+size_t fwd_workspace_bytes(const l2a_params& p) { return use_mfma(p) ? 2 * kv_copy_bytes(p) + redo_bytes(p) : 0; }
 
 int bwd_dq(const l2a_params& p, const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v,
            const void* dO, const float* lse, float* delta, void* dq, int acc, hipStream_t st) {
@@ -87,8 +93,8 @@ size_t l2a_route_workspace_bytes(const l2a_params* p) {
 
 size_t l2a_attn_workspace_bytes(const l2a_params* p, int backward) {
     if (check_params(p) != L2A_OK) return 0;
-    if (!backward) return 0;
-    return 2 * sizeof(float) * stat_elems(*p);  // delta of each branch
+    if (!backward) return fwd_workspace_bytes(*p);  // token-minor copies of V (one per branch)
+    return 2 * sizeof(float) * stat_elems(*p);      // delta of each branch
 }
 
 int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
@@ -107,8 +113,6 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
                  const int32_t* count, const int32_t* kblk_first_row, void* O, float* lse_local,
                  float* lse_global, void* S_opt, void* A_opt, void* workspace, size_t workspace_bytes,
                  void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     (void)kblk_first_row;
     const int rc = check_params(p);
     if (rc != L2A_OK) return rc;
@@ -122,10 +126,30 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
     const void* ptrs[] = {q_loc, k_loc, v_loc, q_glb, k_glb, v_glb, O, S_opt, A_opt};
     for (const void* x : ptrs)
         if (x && misaligned(x)) return L2A_ERR_ALIGN;
+    const size_t need = fwd_workspace_bytes(*p);
+    if (need && (!workspace || workspace_bytes < need)) return L2A_ERR_WORKSPACE;
+    if (need && misaligned(workspace)) return L2A_ERR_ALIGN;
 
     hipStream_t st = (hipStream_t)stream;
     const Geom g = make_geom(*p);
+    const bool mfma = use_mfma(*p);
     int r = L2A_OK;
+    // matrix-core path: token-minor copy of each distinct V (layout pre-pass, one pass over V)
+    char* vt_loc = (char*)workspace;
+    char* vt_glb = vt_loc;
+    if (mfma) {
+        if (do_local && (r = pack_kv(g, v_loc, vt_loc, kv_cap(*p), st)) != L2A_OK) return r;
+        if (do_global && (!do_local || v_glb != v_loc)) {
+            vt_glb = (char*)workspace + kv_copy_bytes(*p);
+            if ((r = pack_kv(g, v_glb, vt_glb, kv_cap(*p), st)) != L2A_OK) return r;
+        }
+    }
+    auto fwd_branch = [&](const RowSet& rs, const void* q, const void* k, const void* v, const void* vt,
+                          const FwdOut& out) {
+        int32_t* redo = (int32_t*)((char*)workspace + 2 * kv_copy_bytes(*p));
+        return mfma ? mfma_fwd(g, rs, q, k, v, vt, kv_cap(*p), redo, out, st)
+                    : simple_fwd(g, p->dtype, rs, q, k, v, out, st);
+    };
     if (do_local) {
         const RowSet rs{nullptr, nullptr, nullptr, 1};
         FwdOut out{O, S_opt, lse_local, nullptr, nullptr, 0};
@@ -133,7 +157,7 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
             out.lse_fill = lse_global;
             out.zero_fill = A_opt;
         }
-        if ((r = fwd_branch(*p, g, rs, q_loc, k_loc, v_loc, out, st)) != L2A_OK) return r;
+        if ((r = fwd_branch(rs, q_loc, k_loc, v_loc, vt_loc, out)) != L2A_OK) return r;
     }
     if (do_global) {
         if (!do_local && !dense) {
@@ -143,7 +167,7 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
         }
         const RowSet rs = dense ? RowSet{nullptr, nullptr, nullptr, 0} : RowSet{row_idx, count, kblk_first_row, 0};
         const FwdOut out{O, A_opt, lse_global, nullptr, nullptr, do_local ? 1 : 0};
-        if ((r = fwd_branch(*p, g, rs, q_glb, k_glb, v_glb, out, st)) != L2A_OK) return r;
+        if ((r = fwd_branch(rs, q_glb, k_glb, v_glb, vt_glb, out)) != L2A_OK) return r;
     }
     return L2A_OK;
 }

@@ -12,6 +12,9 @@
 //   16 half + 4 h + {0,1,2,3}  and  16 half + 8 + 4 h + {0,1,2,3},
 // and the other operand is read from LDS in that same order (two 8-byte reads of a transposed tile).
 #pragma once
+#include <type_traits>
+#include <utility>
+
 #include "common.hpp"
 
 namespace l2a {
@@ -24,6 +27,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// compile-time loop: f(std::integral_constant<int, I>{}) for I = BEGIN .. END-1
+template <int BEGIN, int END, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
 
 constexpr int kD = 128;         // head size
 constexpr int kThreads = 256;   // 4 wavefronts

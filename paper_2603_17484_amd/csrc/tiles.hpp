@@ -1,0 +1,104 @@
+// LDS tiles of the matrix-core kernels and their direct global->LDS loads (gfx950).
+//
+// Every matrix-core operand is read from LDS with one 16-byte ds_read_b128 per lane.  To make
+// that possible for operands whose contracted index is the token (V in P V, K in dS K, Q and dO
+// in dS^T Q and P^T dO), a pre-pass writes *token-minor* copies of those tensors, [.., D, tokens],
+// in which every group of 16 tokens is stored in the order
+//      0 1 2 3  8 9 10 11 | 4 5 6 7  12 13 14 15
+// i.e. position p holds token (p & 3) + 8 ((p >> 2) & 1) + 4 (p >> 3).  The first eight
+// positions are exactly the contracted indices a lane of the lower half-wave needs for one
+// MFMA (see mfma.hpp), the last eight those of the upper half-wave.
+//
+// Tiles are filled by global_load_lds_dwordx4: each lane names its own global address and the
+// hardware writes the 64 lanes' 16-byte pieces to 1024 consecutive LDS bytes starting at M0.
+// No staging registers, no LDS store instructions.  Since the LDS side is fixed, bank conflicts
+// are avoided by permuting on the global side: 16-byte chunk c of a row lands in chunk slot
+// c ^ f(row), and readers apply the same XOR.
+#pragma once
+#include "mfma.hpp"
+
+namespace l2a {
+
+__device__ __forceinline__ unsigned lds_offset(const void* p) {
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// 64 lanes x 16 bytes: lane l's 16 bytes at `gptr` -> LDS bytes [lds_base + 16 l, +16).
+// lds_base must be wave-uniform.  Completion is tracked by vmcnt (dma_wait).
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
+}
+// 64 lanes x 4 bytes
+__device__ __forceinline__ void dma4(const void* gptr, unsigned lds_base) {
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(base), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// ---------------------------------------------------------------------------------------
+// Row-major tile: ROWS tokens x 128 channels, 256-byte rows, chunk c of row r in slot c ^ (r & 15).
+// ---------------------------------------------------------------------------------------
+constexpr int kRmRowBytes = 256;
+
+// row_ptr(r) -> global address of channel 0 of tile row r (must be valid for every r < ROWS).
+// Executed by all 256 threads of the workgroup.
+template <int ROWS, typename RowPtr>
+__device__ __forceinline__ void dma_rm_tile(unsigned lds_base, RowPtr row_ptr) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < ROWS / 16; ++i) {
+        const int seg = i * 4 + wave;  // 1024-byte segment = 4 rows
+        const int row = seg * 4 + (lane >> 4);
+        const int c = (lane & 15) ^ (row & 15);
+        dma16(row_ptr(row) + c * 8, lds_base + seg * 1024);
+    }
+}
+
+// MFMA operand: row `row`, channels 16 ks + 8 h .. + 7
+__device__ __forceinline__ bf16x8 rm_operand(const __bf16* tile, int row, int ks, int h) {
+    const int slot = (2 * ks + h) ^ (row & 15);
+    return *reinterpret_cast<const bf16x8*>(tile + row * 128 + slot * 8);
+}
+
+// ---------------------------------------------------------------------------------------
+// Token-minor tile: 128 channels x TOK tokens (TOK = 64 or 32), rows of 2 TOK bytes.
+// ---------------------------------------------------------------------------------------
+template <int TOK>
+__device__ __forceinline__ int tm_swizzle(int ch) {
+    if (TOK == 64) return (ch & 7) ^ ((ch >> 3) & 1);  // 8 chunks per 128-byte row
+    return ((ch >> 1) ^ (ch >> 3)) & 3;                // 4 chunks per 64-byte row
+}
+
+// src: global address of (channel 0, first token of the tile); ch_stride in elements.
+template <int TOK>
+__device__ __forceinline__ void dma_tm_tile(unsigned lds_base, const __bf16* src, size_t ch_stride) {
+    constexpr int kChunks = TOK / 8;           // 16-byte chunks per row
+    constexpr int kRowsPerSeg = 64 / kChunks;  // rows per 1024-byte segment
+    constexpr int kSegs = 128 / kRowsPerSeg;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < kSegs / 4; ++i) {
+        const int seg = i * 4 + wave;
+        const int ch = seg * kRowsPerSeg + lane / kChunks;
+        const int c = (lane % kChunks) ^ tm_swizzle<TOK>(ch);
+        dma16(src + (size_t)ch * ch_stride + c * 8, lds_base + seg * 1024);
+    }
+}
+
+// MFMA operand: channel `ch`, the eight tokens of 16-token group `step` that half-wave h contracts
+template <int TOK>
+__device__ __forceinline__ bf16x8 tm_operand(const __bf16* tile, int ch, int step, int h) {
+    const int slot = (2 * step + h) ^ tm_swizzle<TOK>(ch);
+    return *reinterpret_cast<const bf16x8*>(tile + ch * TOK + slot * 8);
+}
+
+// position of token t inside its 16-token group in a token-minor copy, and the inverse
+__device__ __host__ __forceinline__ int tm_pos_of_token(int t) {
+    return (t & ~15) | ((t & 3) + 4 * ((t >> 3) & 1) + 8 * ((t >> 2) & 1));
+}
+__device__ __host__ __forceinline__ int tm_token_at_pos(int p) {
+    return (p & ~15) | ((p & 3) + 8 * ((p >> 2) & 1) + 4 * ((p >> 3) & 1));
+}
+
+}  // namespace l2a

@@ -51,6 +51,7 @@ class Layer:
         else:
             self.row_idx, self.count, self.first, self.route_ws = B.alloc_route(p, dev)
         self.O, self.lse_l, self.lse_g, self.S, self.A = B.alloc_fwd(p, dev)
+        self.fwd_ws = B.alloc_fwd_workspace(p, dev)
         self.dq = self.dk = self.dv = self.bwd_ws = None
         self.dqg = self.dkg = self.dvg = None
         self.delta_g = None
@@ -63,7 +64,7 @@ class Layer:
     def forward(self, save_branches: bool = True):
         B.l2a_attn_fwd(self.p, self.q, self.k, self.v, self.qg, self.kg, self.vg, self.row_idx, self.count,
                        self.first, self.O, self.lse_l, self.lse_g, self.S if save_branches else None,
-                       self.A if save_branches else None)
+                       self.A if save_branches else None, self.fwd_ws)
 
     def backward(self, dO: torch.Tensor, separate: bool = False, want_delta: bool = False):
         if self.dq is None:
