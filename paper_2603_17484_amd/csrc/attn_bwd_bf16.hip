@@ -4,10 +4,7 @@
 // of softmax attention:
 //     P = exp(scale Q K^T - lse),  dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),
 //     dQ = scale dS K,  dK = scale dS^T Q,       delta_t = <dO_t, out_t>.
-// Two kernels, no atomics, bit-reproducible:
-//   bwd_dq_kernel   : one workgroup per tile of rows (as the forward); streams K/V blocks.
-//                     Also emits delta_t = sum_j P_tj dP_tj, which equals <dO_t, out_t> without
-//                     the rounding of the saved bf16 output; the dK/dV kernel uses that value.
+// dK and dV (the dQ kernel lives in attn_bwd_dq_bf16.hip); no atomics, bit-reproducible:
 //   bwd_dkdv_kernel : one workgroup per block of 128 keys; streams tiles of 64 rows, first the
 //                     Local rows that can see the block, then the compacted Global rows from
 //                     kblk_first_row on.  The G heads of a KV group are rows of the same list,
@@ -20,201 +17,6 @@ namespace l2a {
 namespace {
 
 constexpr int kBK = 64;
-
-// ======================================================================================
-// dQ
-// ======================================================================================
-struct DqArgs {
-    Geom gm;
-    RowSet rs;
-    const __bf16* q;
-    const __bf16* k;
-    const __bf16* v;
-    const __bf16* dO;
-    const float* lse;
-    float* delta;  // in: <dO, saved out>; out: sum_j P dP
-    __bf16* dq;
-    int accumulate;
-};
-
-template <int NQB, bool LOCAL>
-__global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
-    constexpr int RW = 32 * NQB;
-    constexpr int BQ = 4 * RW;
-    __shared__ __attribute__((aligned(16))) __bf16 lds_k[2][kTileRows * kRowPad];
-    __shared__ __attribute__((aligned(16))) __bf16 lds_kt[2][kD * kColPad];
-    __shared__ __attribute__((aligned(16))) __bf16 lds_v[2][kTileRows * kRowPad];
-
-    const Geom& gm = a.gm;
-    const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
-    const int n_rows = rows_total(a.rs, gm, bh);
-    const int n_tiles = (n_rows + BQ - 1) / BQ;
-    if ((int)blockIdx.x >= n_tiles) return;
-    const int tile = n_tiles - 1 - (int)blockIdx.x;
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n = lane & 31, h = lane >> 5;
-
-    const int wg_r0 = tile * BQ;
-    const int wg_r1 = min(wg_r0 + BQ, n_rows);
-    const int wg_pmin = row_code(a.rs, gm, bh, wg_r0) / gm.G;
-    const int wg_pmax = row_code(a.rs, gm, bh, wg_r1 - 1) / gm.G;
-    const int wv_r0 = wg_r0 + wave * RW;
-    const bool wave_active = wv_r0 < n_rows;
-    const int wv_r1 = min(wv_r0 + RW, n_rows);
-    int wv_pmin = 0, wv_pmax = 0;
-    if (wave_active) {
-        wv_pmin = row_code(a.rs, gm, bh, wv_r0) / gm.G;
-        wv_pmax = row_code(a.rs, gm, bh, wv_r1 - 1) / gm.G;
-    }
-
-    int pos[NQB], head[NQB];
-    bool valid[NQB];
-    float lse2[NQB], dlt[NQB], dlt_exact[NQB];
-    bf16x8 qreg[NQB][8], greg[NQB][8];
-#pragma unroll
-    for (int c = 0; c < NQB; ++c) {
-        const int r = wv_r0 + c * 32 + n;
-        valid[c] = r < n_rows;
-        const int code = row_code(a.rs, gm, bh, min(r, n_rows - 1));
-        pos[c] = code / gm.G;
-        head[c] = hk * gm.G + (code - pos[c] * gm.G);
-        const size_t off = (((size_t)b * gm.T + pos[c]) * gm.Hq + head[c]) * kD + 8 * h;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            qreg[c][ks] = *reinterpret_cast<const bf16x8*>(a.q + off + ks * 16);
-            greg[c][ks] = *reinterpret_cast<const bf16x8*>(a.dO + off + ks * 16);
-        }
-        const size_t so = ((size_t)b * gm.Hq + head[c]) * gm.T + pos[c];
-        lse2[c] = a.lse[so] * kLog2e;
-        dlt[c] = a.delta[so];
-        dlt_exact[c] = 0.f;
-    }
-
-    const int jb0 = LOCAL ? max(wg_pmin - gm.W, 0) / kBK : 0;
-    const int jb1 = wg_pmax / kBK;
-
-    const size_t kv_row = (size_t)gm.Hkv * kD;
-    const __bf16* kbase = a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
-    const __bf16* vbase = a.v + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
-    const int r4 = (threadIdx.x >> 4) * 4;
-    TileRegs kr, vr;
-    auto load_block = [&](int jb) {
-        const int k0 = jb * kBK + r4;
-        tile_load(kr, [&](int i) { return kbase + (size_t)min(k0 + i, gm.T - 1) * kv_row; });
-        tile_load(vr, [&](int i) { return vbase + (size_t)min(k0 + i, gm.T - 1) * kv_row; });
-    };
-    auto store_block = [&](int buf) {
-        tile_store_rowmajor(kr, lds_k[buf]);
-        tile_store_transposed(kr, lds_kt[buf]);
-        tile_store_rowmajor(vr, lds_v[buf]);
-    };
-
-    f32x16 acc[4][NQB];
-#pragma unroll
-    for (int c = 0; c < NQB; ++c)
-#pragma unroll
-        for (int d = 0; d < 4; ++d)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[d][c][r] = 0.f;
-
-    load_block(jb0);
-    store_block(0);
-    __syncthreads();
-
-    for (int jb = jb0; jb <= jb1; ++jb) {
-        const int cur = (jb - jb0) & 1;
-        if (jb < jb1) load_block(jb + 1);
-
-        const int k0 = jb * kBK;
-        bool skip = !wave_active || k0 > wv_pmax;
-        if (LOCAL) skip = skip || (k0 + kBK - 1 < wv_pmin - gm.W);
-        if (!skip) {
-            bool need_mask = k0 + kBK - 1 > wv_pmin;
-            if (LOCAL) need_mask = need_mask || (k0 < wv_pmax - gm.W);
-            const __bf16* ks_ = lds_k[cur];
-            const __bf16* kt_ = lds_kt[cur];
-            const __bf16* vs_ = lds_v[cur];
-
-            bf16x8 dsb[NQB][4];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                // S^T = K Q^T and dP^T = V dO^T for 32 keys
-                f32x16 s[NQB], dp[NQB];
-#pragma unroll
-                for (int c = 0; c < NQB; ++c)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        s[c][r] = 0.f;
-                        dp[c][r] = 0.f;
-                    }
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 ak = lds_rowmajor(ks_, kb * 32 + n, ks, h);
-                    const bf16x8 av = lds_rowmajor(vs_, kb * 32 + n, ks, h);
-#pragma unroll
-                    for (int c = 0; c < NQB; ++c) {
-                        s[c] = mfma32(ak, qreg[c][ks], s[c]);
-                        dp[c] = mfma32(av, greg[c][ks], dp[c]);
-                    }
-                }
-#pragma unroll
-                for (int c = 0; c < NQB; ++c) {
-                    float dsum = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float p = fast_exp2(fmaf(s[c][r], gm.scale_log2, -lse2[c]));
-                        if (need_mask) {
-                            const int key = k0 + kb * 32 + c_row(r, h);
-                            bool ok = key <= pos[c];
-                            if (LOCAL) ok = ok && (key >= pos[c] - gm.W);
-                            p = ok ? p : 0.f;
-                        }
-                        dsum = fmaf(p, dp[c][r], dsum);
-                        s[c][r] = p * (dp[c][r] - dlt[c]);
-                    }
-                    dlt_exact[c] += dsum;
-                    dsb[c][kb * 2 + 0] = pack8(s[c], 0);
-                    dsb[c][kb * 2 + 1] = pack8(s[c], 1);
-                }
-            }
-            // dQ^T += K^T dS^T
-#pragma unroll
-            for (int step = 0; step < 4; ++step)
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const bf16x8 akt = lds_transposed(kt_, d * 32 + n, step, h);
-#pragma unroll
-                    for (int c = 0; c < NQB; ++c) acc[d][c] = mfma32(akt, dsb[c][step], acc[d][c]);
-                }
-        }
-
-        if (jb < jb1) store_block(cur ^ 1);
-        __syncthreads();
-    }
-
-    if (!wave_active) return;
-#pragma unroll
-    for (int c = 0; c < NQB; ++c) {
-        const float de = dlt_exact[c] + __shfl_xor(dlt_exact[c], 32);
-        if (!valid[c]) continue;
-        const size_t base = (((size_t)b * gm.T + pos[c]) * gm.Hq + head[c]) * kD + 4 * h;
-#pragma unroll
-        for (int d = 0; d < 4; ++d)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const size_t off = base + d * 32 + 8 * rg;
-                f32x4 x = {acc[d][c][4 * rg + 0] * gm.scale, acc[d][c][4 * rg + 1] * gm.scale,
-                           acc[d][c][4 * rg + 2] * gm.scale, acc[d][c][4 * rg + 3] * gm.scale};
-                if (a.accumulate) {
-                    const bf16x4 old = *reinterpret_cast<const bf16x4*>(a.dq + off);
-                    x += __builtin_convertvector(old, f32x4);
-                }
-                *reinterpret_cast<bf16x4*>(a.dq + off) = __builtin_convertvector(x, bf16x4);
-            }
-        if (h == 0) a.delta[((size_t)b * gm.Hq + head[c]) * gm.T + pos[c]] = de;
-    }
-}
 
 // ======================================================================================
 // dK, dV
@@ -582,30 +384,6 @@ int env_int(const char* name, int dflt) {
 }
 
 }  // namespace
-
-int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,
-                const float* lse, float* delta, void* dq, int accumulate, hipStream_t st) {
-    if (g.D != kD) return L2A_ERR_UNSUPPORTED;
-    static const int nqb = env_int("L2A_DQ_NQB", 1);
-    DqArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dO, lse, delta,
-             (__bf16*)dq, accumulate};
-    const long long rows = (long long)g.T * g.G;
-    const int bq = 128 * (nqb == 2 ? 2 : 1);
-    const dim3 grid((unsigned)((rows + bq - 1) / bq), g.B * g.Hkv);
-    KernelTimer kt(rs.local ? "bwd_dq_local" : "bwd_dq_global", st);
-    if (nqb == 2) {
-        if (rs.local)
-            hipLaunchKernelGGL((bwd_dq_kernel<2, true>), grid, dim3(kThreads), 0, st, a);
-        else
-            hipLaunchKernelGGL((bwd_dq_kernel<2, false>), grid, dim3(kThreads), 0, st, a);
-    } else {
-        if (rs.local)
-            hipLaunchKernelGGL((bwd_dq_kernel<1, true>), grid, dim3(kThreads), 0, st, a);
-        else
-            hipLaunchKernelGGL((bwd_dq_kernel<1, false>), grid, dim3(kThreads), 0, st, a);
-    }
-    return launch_status();
-}
 
 int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* q, const void* k, const void* v,
                   const void* dO, const float* const* lse, const float* const* delta, void* dk, void* dv,

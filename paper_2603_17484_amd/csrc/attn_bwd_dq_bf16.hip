@@ -1,0 +1,269 @@
+// Backward kernel for dQ, bf16 on the matrix cores (gfx950).  Gradients are taken only for the
+// rows of a branch's row set -- the routed queries for the Global branch -- with the saved
+// log-sum-exp (Sec. 3.2).  Standard softmax-attention gradient:
+//     P = exp(scale Q K^T - lse),  dP = dO V^T,  dS = P o (dP - delta),  dQ = scale dS K.
+// The kernel also emits delta_t = sum_j P_tj dP_tj, which equals <dO_t, out_t> without the
+// rounding of the saved bf16 output; the dK/dV kernel uses that value.
+//
+// Same decomposition as the forward: a workgroup owns a tile of consecutive rows (4 wavefronts
+// x 32 rows), a lane owns a row, everything is computed transposed:
+//   S^T  = K Q^T        A = K block (LDS),            B = Q  (registers)
+//   dP^T = V dO^T       A = V block (LDS),            B = dO (registers)
+//   dQ^T += K^T dS^T    A = K block, token-minor (LDS), B = dS^T = the accumulators above
+// K, V and the token-minor copy of K stream through LDS by direct global->LDS loads.
+// Software pipeline per 32 keys (24 matrix-core instructions = 24 slots): the scores of the next
+// half-block (slots 0-15) and the dQ update of this one (slots 16-23) run on the matrix cores
+// while the VALU turns this half-block's S, dP into dS.
+#include "tiles.hpp"
+
+namespace l2a {
+namespace {
+
+constexpr int kBK = 64;
+constexpr int kRW = 32;        // rows per wavefront
+constexpr int kBQ = 4 * kRW;   // rows per workgroup
+constexpr int kAhead = 3;      // operand look-ahead, in slots
+
+#define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int V>
+using Int = std::integral_constant<int, V>;
+
+struct DqArgs {
+    Geom gm;
+    RowSet rs;
+    const __bf16* q;
+    const __bf16* k;
+    const __bf16* v;
+    const __bf16* kt;  // token-minor copy of K: [B*Hkv][128][kt_cap]
+    int kt_cap;
+    const __bf16* dO;
+    const float* lse;
+    float* delta;  // in: <dO, saved out>; out: sum_j P dP
+    __bf16* dq;
+    int accumulate;
+};
+
+struct SdP {
+    f32x16 s, dp;  // 32 keys x 32 rows each
+};
+
+template <bool LOCAL>
+__global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_v[3][kBK * 128];
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_kt[2][kD * kBK];
+
+    const Geom& gm = a.gm;
+    const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
+    const int n_rows = rows_total(a.rs, gm, bh);
+    const int n_tiles = (n_rows + kBQ - 1) / kBQ;
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int tile = n_tiles - 1 - (int)blockIdx.x;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, h = lane >> 5;
+
+    const int wg_r0 = tile * kBQ;
+    const int wg_r1 = min(wg_r0 + kBQ, n_rows);
+    const int wg_pmin = row_code(a.rs, gm, bh, wg_r0) / gm.G;
+    const int wg_pmax = row_code(a.rs, gm, bh, wg_r1 - 1) / gm.G;
+    const int wv_r0 = wg_r0 + wave * kRW;
+    const bool wave_active = wv_r0 < n_rows;
+
+    // ---- this lane's row: Q and dO stay in registers as B operands
+    const int r = wv_r0 + n;
+    const bool valid = r < n_rows;
+    const int code = row_code(a.rs, gm, bh, min(r, n_rows - 1));  // rows past the end repeat the last one
+    const int pos = code / gm.G;
+    const int head = hk * gm.G + (code - pos * gm.G);
+    const size_t row_off = (((size_t)b * gm.T + pos) * gm.Hq + head) * kD;
+    const size_t so = ((size_t)b * gm.Hq + head) * gm.T + pos;
+    bf16x8 qreg[8], greg[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        qreg[ks] = *reinterpret_cast<const bf16x8*>(a.q + row_off + 8 * h + ks * 16);
+        greg[ks] = *reinterpret_cast<const bf16x8*>(a.dO + row_off + 8 * h + ks * 16);
+    }
+    const float neg_lse2 = -a.lse[so] * kLog2e;
+    const float dlt = a.delta[so];
+    float dlt_exact = 0.f;
+
+    // ---- block range and its three runs (window-start masks / no masks / causal diagonal)
+    const int jb0 = LOCAL ? max(wg_pmin - gm.W, 0) / kBK : 0;
+    const int jb1 = wg_pmax / kBK;
+    int j_mid = jb0;
+    if (LOCAL) j_mid = min(jb1 + 1, max(jb0, (max(wg_pmax - gm.W, 0) + kBK - 1) / kBK));
+    const int j_diag = max(j_mid, min(jb1 + 1, (wg_pmin + 1) / kBK));
+
+    const size_t kv_row = (size_t)gm.Hkv * kD;
+    const __bf16* kbase = a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
+    const __bf16* vbase = a.v + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
+    const __bf16* ktbase = a.kt + (size_t)bh * kD * a.kt_cap;
+    const unsigned lds_k0 = lds_offset(&lds_k[0][0]), lds_v0 = lds_offset(&lds_v[0][0]);
+    const unsigned lds_kt0 = lds_offset(&lds_kt[0][0]);
+    auto load_kv = [&](int jb, int buf) __attribute__((always_inline)) {
+        // keys past the end of the sequence are clamped: always masked, never out of bounds
+        dma_rm_tile<kBK>(lds_k0 + buf * (kBK * 256),
+                         [&](int rr) { return kbase + (size_t)min(jb * kBK + rr, gm.T - 1) * kv_row; });
+        dma_rm_tile<kBK>(lds_v0 + buf * (kBK * 256),
+                         [&](int rr) { return vbase + (size_t)min(jb * kBK + rr, gm.T - 1) * kv_row; });
+    };
+    auto load_kt = [&](int jb, int buf) __attribute__((always_inline)) {
+        dma_tm_tile<kBK>(lds_kt0 + buf * (kD * kBK * 2), ktbase + (size_t)jb * kBK, (size_t)a.kt_cap);
+    };
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[d][e] = 0.f;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // One half-block (32 keys k0..k0+31, half KB of its block): dS from `cur`, overlapped with S, dP
+    // of the next half-block into `nxt` (rows krow0.. of tiles kt_, vt_) and dQ += K^T dS (tile ktt).
+    auto half_block = [&](auto mask_tag, auto kb_tag, SdP& cur, SdP& nxt, const __bf16* kt_, const __bf16* vt_,
+                          int krow0, const __bf16* ktt, int k0) __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        constexpr int KB = decltype(kb_tag)::value;
+        const float c2 = gm.scale_log2;
+        bf16x8 opnd[24 + kAhead];
+        uint32_t dsw[2][4];  // dS as packed bf16 pairs: [16-key group][dword]
+        float dsum = 0.f;
+        // operand of slot m: m < 16 -> K (even) / V (odd) rows of the next half-block, ks = m / 2;
+        // else token-minor K: (16-key group, channel block)
+        auto read_operand = [&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            if constexpr (mm < 16) {
+                if constexpr ((mm & 1) == 0) opnd[mm] = rm_operand(kt_, krow0 + n, mm >> 1, h);
+                else opnd[mm] = rm_operand(vt_, krow0 + n, mm >> 1, h);
+            } else if constexpr (mm < 24) {
+                opnd[mm] = tm_operand<kBK>(ktt, ((mm - 16) & 3) * 32 + n, 2 * KB + ((mm - 16) >> 2), h);
+            }
+        };
+        auto issue = [&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            if constexpr (mm < 16) {
+                constexpr int ks = mm >> 1;
+                if constexpr ((mm & 1) == 0) nxt.s = mfma32(opnd[mm], qreg[ks], ks == 0 ? zero16 : nxt.s);
+                else nxt.dp = mfma32(opnd[mm], greg[ks], ks == 0 ? zero16 : nxt.dp);
+            } else {
+                constexpr int x = mm - 16, grp = x >> 2, d = x & 3;
+                const u32x4 dv = {dsw[grp][0], dsw[grp][1], dsw[grp][2], dsw[grp][3]};
+                acc[d] = mfma32(opnd[mm], __builtin_bit_cast(bf16x8, dv), acc[d]);
+            }
+        };
+        auto ds_pair = [&](auto qc) {  // pair q in 0..7, in the order the dQ product consumes them
+            constexpr int q = decltype(qc)::value;
+            constexpr int grp = q >> 2, i2 = (q & 3) * 2, e = grp * 8 + i2;
+            float p0 = fast_exp2(fmaf(cur.s[e], c2, neg_lse2));
+            float p1 = fast_exp2(fmaf(cur.s[e + 1], c2, neg_lse2));
+            if (MASK) {
+                const int key0 = k0 + c_row(e, h), key1 = k0 + c_row(e + 1, h);
+                bool ok0 = key0 <= pos, ok1 = key1 <= pos;
+                if (LOCAL) {
+                    ok0 = ok0 && (key0 >= pos - gm.W);
+                    ok1 = ok1 && (key1 >= pos - gm.W);
+                }
+                p0 = ok0 ? p0 : 0.f;
+                p1 = ok1 ? p1 : 0.f;
+            }
+            const float dp0 = cur.dp[e], dp1 = cur.dp[e + 1];
+            dsum = fmaf(p0, dp0, fmaf(p1, dp1, dsum));
+            f32x2 f = {p0 * (dp0 - dlt), p1 * (dp1 - dlt)};
+            dsw[grp][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+        };
+
+        static_for<0, kAhead>([&](auto mc) { read_operand(mc); });
+        L2A_FENCE();
+        static_for<0, 24>([&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            issue(mc);
+            read_operand(Int<mm + kAhead>{});
+            static_for<0, 8>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                if constexpr ((q * 7) / 4 == mm) ds_pair(qc);
+            });
+            L2A_FENCE();
+        });
+        dlt_exact += dsum;
+    };
+
+    // ---- prologue: K, V of the first two blocks, token-minor K of the first; S, dP of the first half-block
+    SdP Xa, Xb;
+    load_kv(jb0, 0);
+    if (jb0 < jb1) load_kv(jb0 + 1, 1);
+    load_kt(jb0, 0);
+    dma_wait();
+    __syncthreads();
+    if (wave_active) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            Xa.s = mfma32(rm_operand(&lds_k[0][0], n, ks, h), qreg[ks], ks == 0 ? zero16 : Xa.s);
+            Xa.dp = mfma32(rm_operand(&lds_v[0][0], n, ks, h), greg[ks], ks == 0 ? zero16 : Xa.dp);
+        }
+    }
+
+    auto run = [&](auto mask_tag, int j_begin, int j_end) __attribute__((always_inline)) {
+        for (int jb = j_begin; jb < j_end; ++jb) {
+            const int rel = jb - jb0;
+            const int buf = rel % 3, buf1 = (rel + 1) % 3, buf2 = (rel + 2) % 3;
+            if (jb + 2 <= jb1) load_kv(jb + 2, buf2);          // that buffer held block jb-1
+            if (jb + 1 <= jb1) load_kt(jb + 1, (rel + 1) & 1);  // held block jb-1
+            if (wave_active) {
+                const __bf16* ktt = &lds_kt[rel & 1][0];
+                half_block(mask_tag, Int<0>{}, Xa, Xb, &lds_k[buf][0], &lds_v[buf][0], 32, ktt, jb * kBK);
+                half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], &lds_v[buf1][0], 0, ktt, jb * kBK + 32);
+            }
+            dma_wait();
+            __syncthreads();
+        }
+    };
+    for (int seg = 0; seg < 3; ++seg) {
+        const int j_begin = seg == 0 ? jb0 : (seg == 1 ? j_mid : j_diag);
+        const int j_end = seg == 0 ? j_mid : (seg == 1 ? j_diag : jb1 + 1);
+        if (seg == 1)
+            run(std::false_type{}, j_begin, j_end);
+        else
+            run(std::true_type{}, j_begin, j_end);
+    }
+
+    // ---- epilogue
+    if (!wave_active) return;
+    const float de = dlt_exact + __shfl_xor(dlt_exact, 32);
+    if (!valid) return;
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+            const size_t off = row_off + 4 * h + d * 32 + 8 * rg;
+            f32x4 x = {acc[d][4 * rg + 0] * gm.scale, acc[d][4 * rg + 1] * gm.scale, acc[d][4 * rg + 2] * gm.scale,
+                       acc[d][4 * rg + 3] * gm.scale};
+            if (a.accumulate) {
+                const bf16x4 old = *reinterpret_cast<const bf16x4*>(a.dq + off);
+                x += __builtin_convertvector(old, f32x4);
+            }
+            *reinterpret_cast<bf16x4*>(a.dq + off) = __builtin_convertvector(x, bf16x4);
+        }
+    if (h == 0) a.delta[so] = de;
+}
+
+}  // namespace
+
+int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* kt,
+                int kt_cap, const void* dO, const float* lse, float* delta, void* dq, int accumulate,
+                hipStream_t st) {
+    if (g.D != kD) return L2A_ERR_UNSUPPORTED;
+    DqArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)kt, kt_cap,
+             (const __bf16*)dO, lse, delta, (__bf16*)dq, accumulate};
+    const long long rows = (long long)g.T * g.G;
+    const dim3 grid((unsigned)((rows + kBQ - 1) / kBQ), g.B * g.Hkv);
+    KernelTimer kt_(rs.local ? "bwd_dq_local" : "bwd_dq_global", st);
+    if (rs.local)
+        hipLaunchKernelGGL((bwd_dq_kernel<true>), grid, dim3(kThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL((bwd_dq_kernel<false>), grid, dim3(kThreads), 0, st, a);
+    return launch_status();
+}
+
+}  // namespace l2a

@@ -87,8 +87,10 @@ int pack_kv(const Geom& g, const void* x, void* xt, int cap, hipStream_t st);
 int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, const float* lse, const float* delta,
               void* qc, void* gc, void* qt, void* gt, float* lse2_c, float* delta_c, int32_t* pos_c, int cap,
               hipStream_t st);
-int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,
-                const float* lse, float* delta, void* dq, int accumulate, hipStream_t st);
+// kt: token-minor copy of k from pack_kv
+int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* kt,
+                int kt_cap, const void* dO, const float* lse, float* delta, void* dq, int accumulate,
+                hipStream_t st);
 int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* q, const void* k, const void* v,
                   const void* dO, const float* const* lse, const float* const* delta, void* dk, void* dv,
                   hipStream_t st);

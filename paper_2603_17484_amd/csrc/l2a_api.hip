@@ -50,12 +50,12 @@ size_t redo_bytes(const l2a_params& p) {
 }
 // two token-minor copies of V (one per branch) and the forward kernels' redo flags
 size_t fwd_workspace_bytes(const l2a_params& p) { return use_mfma(p) ? 2 * kv_copy_bytes(p) + redo_bytes(p) : 0; }
-
-int bwd_dq(const l2a_params& p, const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v,
-           const void* dO, const float* lse, float* delta, void* dq, int acc, hipStream_t st) {
-    return use_mfma(p) ? mfma_bwd_dq(g, rs, q, k, v, dO, lse, delta, dq, acc, st)
-                       : simple_bwd_dq(g, p.dtype, rs, q, k, v, dO, lse, delta, dq, acc, st);
+// backward: delta of each branch; matrix-core path: + token-minor copies of K (one per branch)
+size_t delta_bytes(const l2a_params& p) { return (sizeof(float) * stat_elems(p) + 255) / 256 * 256; }
+size_t bwd_workspace_bytes(const l2a_params& p) {
+    return 2 * delta_bytes(p) + (use_mfma(p) ? 2 * kv_copy_bytes(p) : 0);
 }
+
 
 int bwd_dkdv(const l2a_params& p, const Geom& g, const RowSet* sets, int n, const void* q, const void* k,
              const void* v, const void* dO, const float* const* lse, const float* const* delta, void* dk, void* dv,
@@ -93,8 +93,8 @@ size_t l2a_route_workspace_bytes(const l2a_params* p) {
 
 size_t l2a_attn_workspace_bytes(const l2a_params* p, int backward) {
     if (check_params(p) != L2A_OK) return 0;
-    if (!backward) return fwd_workspace_bytes(*p);  // token-minor copies of V (one per branch)
-    return 2 * sizeof(float) * stat_elems(*p);      // delta of each branch
+    if (!backward) return fwd_workspace_bytes(*p);
+    return bwd_workspace_bytes(*p);
 }
 
 int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
@@ -203,9 +203,24 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
 
     hipStream_t st = (hipStream_t)stream;
     const Geom g = make_geom(*p);
-    float* delta_l = (float*)workspace;
-    float* delta_g = delta_glb_opt ? delta_glb_opt : delta_l + stat_elems(*p);
     int r;
+    float* delta_l = (float*)workspace;
+    float* delta_g = delta_glb_opt ? delta_glb_opt : (float*)((char*)workspace + delta_bytes(*p));
+    const bool mfma = use_mfma(*p);
+    char* kt_loc = (char*)workspace + 2 * delta_bytes(*p);
+    char* kt_glb = kt_loc;
+    if (mfma) {  // token-minor copy of each distinct K (layout pre-pass)
+        if (do_local && (r = pack_kv(g, k_loc, kt_loc, kv_cap(*p), st)) != L2A_OK) return r;
+        if (do_global && (!do_local || k_glb != k_loc)) {
+            kt_glb = kt_loc + kv_copy_bytes(*p);
+            if ((r = pack_kv(g, k_glb, kt_glb, kv_cap(*p), st)) != L2A_OK) return r;
+        }
+    }
+    auto bwd_dq = [&](const RowSet& rs, const void* q, const void* k, const void* v, const void* kt, const float* lse,
+                      float* delta, void* dq, int acc) {
+        return mfma ? mfma_bwd_dq(g, rs, q, k, v, kt, kv_cap(*p), dO, lse, delta, dq, acc, st)
+                    : simple_bwd_dq(g, p->dtype, rs, q, k, v, dO, lse, delta, dq, acc, st);
+    };
     if ((r = row_deltas(g, p->dtype, dO, do_local ? S : nullptr, do_global ? A : nullptr, delta_l, delta_g, st)) !=
         L2A_OK)
         return r;
@@ -214,12 +229,10 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
     const RowSet rs_g = dense ? RowSet{nullptr, nullptr, nullptr, 0} : RowSet{row_idx, count, kblk_first_row, 0};
 
     // dQ: one pass per branch over that branch's rows
-    if (do_local && (r = bwd_dq(*p, g, rs_l, q_loc, k_loc, v_loc, dO, lse_local, delta_l, dq_loc, 0, st)) != L2A_OK)
-        return r;
+    if (do_local && (r = bwd_dq(rs_l, q_loc, k_loc, v_loc, kt_loc, lse_local, delta_l, dq_loc, 0)) != L2A_OK) return r;
     if (do_global) {
         if (!out_alias && !dense && (r = fill_zero(dq_glb, q_elems(*p) * elem_bytes(*p), st)) != L2A_OK) return r;
-        if ((r = bwd_dq(*p, g, rs_g, q_glb, k_glb, v_glb, dO, lse_global, delta_g, dq_glb, out_alias ? 1 : 0, st)) !=
-            L2A_OK)
+        if ((r = bwd_dq(rs_g, q_glb, k_glb, v_glb, kt_glb, lse_global, delta_g, dq_glb, out_alias ? 1 : 0)) != L2A_OK)
             return r;
     }
     // dK, dV: one pass over the key tokens; with shared inputs both branches accumulate in registers
