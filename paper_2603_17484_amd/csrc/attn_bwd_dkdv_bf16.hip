@@ -1,0 +1,349 @@
+// Backward kernel for dK and dV, bf16 on the matrix cores (gfx950).  Gradients come only from
+// the rows of each branch's row set -- the routed queries for the Global branch (Sec. 3.2).
+//     P = exp(scale Q K^T - lse),  dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dK = scale dS^T Q.
+// No atomics, bit-reproducible: one workgroup owns a block of 128 keys (4 wavefronts x 32 keys)
+// and streams tiles of 32 rows: first the Local rows that can see the block, then the compacted
+// Global rows from kblk_first_row on.  The G heads of a KV group are rows of the same list, so
+// the sum over the heads of a group needs no second pass.
+//
+// Rows are read from the compact copies the pack pre-pass makes of each branch's Q and dO
+// (row-major for S = Q K^T and dP = dO V^T, token-minor for dV += P^T dO and dK += dS^T Q)
+// together with the rows' log-sum-exp, delta and position, by direct global->LDS loads.
+//   S  [row, key] = Q K^T     A = Q tile (LDS, row-major),  B = K (registers, loaded once)
+//   dP [row, key] = dO V^T    A = dO tile,                   B = V (registers)
+//   dV [key, ch] += P^T dO    A = P^T  = the S accumulators,  B = dO tile (LDS, token-minor)
+//   dK [key, ch] += dS^T Q    A = dS^T = the dP accumulators, B = Q tile (LDS, token-minor)
+// Software pipeline per tile (32 matrix-core instructions = 32 slots): S, dP of the next tile
+// (slots 0-15) and the dV, dK update of this tile (slots 16-31) run on the matrix cores while the
+// VALU turns this tile's S, dP into P and dS.
+#include "tiles.hpp"
+
+namespace l2a {
+namespace {
+
+constexpr int kKeysPerWg = 128;
+constexpr int kRT = 32;     // rows per tile
+constexpr int kAhead = 3;   // operand look-ahead, in slots
+
+#define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int V>
+using Int = std::integral_constant<int, V>;
+
+struct PackedRows {   // compact copies of one branch's rows, per (b, kv head): cap rows
+    const __bf16* qc;   // [nbh][cap][128]
+    const __bf16* gc;   // dO
+    const __bf16* qt;   // [nbh][128][cap], token-minor
+    const __bf16* gt;
+    const float* lse2;  // [nbh][cap]  lse * log2(e)
+    const float* delta;
+    const int32_t* pos; // -1 = padding
+};
+
+struct DkdvArgs {
+    Geom gm;
+    RowSet rs[2];
+    PackedRows rows[2];
+    int nsets;
+    int cap;
+    const __bf16* k;
+    const __bf16* v;
+    __bf16* dk;
+    __bf16* dv;
+};
+
+struct RowTileLds {
+    __bf16 q_rm[kRT * 128];
+    __bf16 g_rm[kRT * 128];
+};
+struct ColTileLds {
+    __bf16 q_t[kD * kRT];
+    __bf16 g_t[kD * kRT];
+    float lse2[64];   // 32 used; a whole wavefront writes 64 entries
+    float delta[64];
+    int pos[64];
+    int pad[64];
+};
+
+struct SdP {
+    f32x16 s, dp;
+};
+
+__global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
+    __shared__ __attribute__((aligned(1024))) RowTileLds lds_rm[2];
+    __shared__ __attribute__((aligned(1024))) ColTileLds lds_tm[2];
+
+    const Geom& gm = a.gm;
+    const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
+    const int k0 = blockIdx.x * kKeysPerWg;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int kw0 = k0 + wave * 32;
+    const int key = kw0 + n;  // this lane's key (a column of S)
+    const int nkb = (gm.T + 63) / 64;
+
+    // ---- the wavefront's 32 keys stay in registers as B operands
+    bf16x8 kreg[8], vreg[8];
+    {
+        const size_t off = (((size_t)b * gm.T + min(key, gm.T - 1)) * gm.Hkv + hk) * kD + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            kreg[ks] = *reinterpret_cast<const bf16x8*>(a.k + off + ks * 16);
+            vreg[ks] = *reinterpret_cast<const bf16x8*>(a.v + off + ks * 16);
+        }
+    }
+
+    // ---- per set: the 32-row tiles that can see this block of keys, split in three runs: a head
+    // whose rows may lie before some key (causal mask), a middle that needs no mask, a tail
+    // (sliding-window edge, ragged end).  Tile t of a set covers rows 32 t .. 32 t + 31.
+    auto tile_runs = [&](int s, int& tb, int& th, int& tt, int& te) __attribute__((always_inline)) {
+        tb = th = tt = te = 0;
+        if (s >= a.nsets) return;
+        const RowSet& rs = a.rs[s];
+        int rb, re, r_mid;
+        const int kend = k0 + kKeysPerWg;  // rows at positions >= kend see every key of the block
+        if (rs.local) {
+            rb = k0 * gm.G;
+            re = min(gm.T, kend + gm.W) * gm.G;
+            r_mid = kend * gm.G;
+        } else if (!rs.kblk_first_row) {  // dense: identity rows
+            rb = k0 * gm.G;
+            re = gm.T * gm.G;
+            r_mid = kend * gm.G;
+        } else {
+            const int32_t* first = rs.kblk_first_row + (size_t)bh * (nkb + 1);
+            rb = first[k0 >> 6];
+            re = rs.count[bh];
+            r_mid = first[min(kend >> 6, nkb)];
+        }
+        if (kend > gm.T) r_mid = re;  // keys past the end of the sequence: mask everywhere
+        if (re <= rb) return;
+        tb = rb / kRT;
+        te = (re + kRT - 1) / kRT;
+        th = min(te, max(tb, (r_mid + kRT - 1) / kRT));
+        int tl = (re % kRT) ? te - 1 : te;
+        if (rs.local) {
+            const long long r_suf = (long long)(k0 + gm.W + 1) * gm.G;  // first row whose window starts after k0
+            if (r_suf < re) tl = min(tl, (int)(r_suf / kRT));
+        }
+        tt = max(tl, th);
+    };
+    int tb0, th0, tt0, te0, tb1, th1, tt1, te1;
+    tile_runs(0, tb0, th0, tt0, te0);
+    tile_runs(1, tb1, th1, tt1, te1);
+    const int n0 = te0 - tb0, n1 = te1 - tb1;
+    const int total = n0 + n1;
+
+    // ---- loads.  Flat tile index it -> (set, tile)
+    const unsigned lds_rm0 = lds_offset(&lds_rm[0]), lds_tm0 = lds_offset(&lds_tm[0]);
+    auto locate = [&](int it, int& s, int& t) __attribute__((always_inline)) {
+        s = it < n0 ? 0 : 1;
+        t = s ? tb1 + (it - n0) : tb0 + it;
+    };
+    auto load_rm = [&](int it, int buf) __attribute__((always_inline)) {
+        int s, t;
+        locate(it, s, t);
+        const __bf16* qc = s ? a.rows[1].qc : a.rows[0].qc;
+        const __bf16* gc = s ? a.rows[1].gc : a.rows[0].gc;
+        const size_t base = ((size_t)bh * a.cap + (size_t)t * kRT) * kD;
+        const unsigned dst = lds_rm0 + buf * (unsigned)sizeof(RowTileLds);
+        dma_rm_tile<kRT>(dst, [&](int r) { return qc + base + (size_t)r * kD; });
+        dma_rm_tile<kRT>(dst + kRT * 256, [&](int r) { return gc + base + (size_t)r * kD; });
+    };
+    auto load_tm = [&](int it, int buf) __attribute__((always_inline)) {
+        int s, t;
+        locate(it, s, t);
+        const PackedRows pr = s ? a.rows[1] : a.rows[0];
+        const size_t base = (size_t)bh * kD * a.cap + (size_t)t * kRT;
+        const unsigned dst = lds_tm0 + buf * (unsigned)sizeof(ColTileLds);
+        dma_tm_tile<kRT>(dst, pr.qt + base, (size_t)a.cap);
+        dma_tm_tile<kRT>(dst + kD * kRT * 2, pr.gt + base, (size_t)a.cap);
+        if (wave == 0) {  // per-row statistics: 32 rows, the upper half-wave repeats the lower one
+            const size_t so = (size_t)bh * a.cap + (size_t)t * kRT + n;
+            dma4(pr.lse2 + so, dst + 2 * kD * kRT * 2);
+            dma4(pr.delta + so, dst + 2 * kD * kRT * 2 + 256);
+            dma4(pr.pos + so, dst + 2 * kD * kRT * 2 + 512);
+        }
+    };
+
+    f32x16 dkacc[4], dvacc[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            dkacc[d][e] = 0.f;
+            dvacc[d][e] = 0.f;
+        }
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // One tile: P, dS from `cur` (tile it; statistics and token-minor tiles in ct) overlapped with
+    // S, dP of tile it+1 into `nxt` (row-major tiles rt) and the dV, dK update of tile it.
+    auto tile_step = [&](auto mask_tag, SdP& cur, SdP& nxt, const RowTileLds& rt, const ColTileLds& ct, bool local)
+                         __attribute__((always_inline)) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        const float c2 = gm.scale_log2;
+        bf16x8 opnd[32 + kAhead];
+        uint32_t pw[2][4], dsw[2][4];  // P^T, dS^T as packed bf16 pairs: [16-row group][dword]
+        f32x4 l2[4], dl[4];
+        i32x4 ps[4];
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {  // register 4 rg + e holds row 8 rg + 4 h + e
+            l2[rg] = *reinterpret_cast<const f32x4*>(&ct.lse2[8 * rg + 4 * h]);
+            dl[rg] = *reinterpret_cast<const f32x4*>(&ct.delta[8 * rg + 4 * h]);
+            if (MASK) ps[rg] = *reinterpret_cast<const i32x4*>(&ct.pos[8 * rg + 4 * h]);
+        }
+        // operand of slot m: m < 16 -> Q (even) / dO (odd) rows of the next tile, ks = m / 2;
+        // else token-minor dO (even) / Q (odd): 16-row group (m - 16) / 8, channel block ((m - 16) / 2) % 4
+        auto read_operand = [&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            if constexpr (mm < 16) {
+                if constexpr ((mm & 1) == 0) opnd[mm] = rm_operand(rt.q_rm, n, mm >> 1, h);
+                else opnd[mm] = rm_operand(rt.g_rm, n, mm >> 1, h);
+            } else if constexpr (mm < 32) {
+                constexpr int x = mm - 16, step = x >> 3, d = (x >> 1) & 3;
+                if constexpr ((x & 1) == 0) opnd[mm] = tm_operand<kRT>(ct.g_t, d * 32 + n, step, h);
+                else opnd[mm] = tm_operand<kRT>(ct.q_t, d * 32 + n, step, h);
+            }
+        };
+        auto issue = [&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            if constexpr (mm < 16) {
+                constexpr int ks = mm >> 1;
+                if constexpr ((mm & 1) == 0) nxt.s = mfma32(opnd[mm], kreg[ks], ks == 0 ? zero16 : nxt.s);
+                else nxt.dp = mfma32(opnd[mm], vreg[ks], ks == 0 ? zero16 : nxt.dp);
+            } else {
+                constexpr int x = mm - 16, step = x >> 3, d = (x >> 1) & 3;
+                if constexpr ((x & 1) == 0) {
+                    const u32x4 pv = {pw[step][0], pw[step][1], pw[step][2], pw[step][3]};
+                    dvacc[d] = mfma32(__builtin_bit_cast(bf16x8, pv), opnd[mm], dvacc[d]);
+                } else {
+                    const u32x4 dv = {dsw[step][0], dsw[step][1], dsw[step][2], dsw[step][3]};
+                    dkacc[d] = mfma32(__builtin_bit_cast(bf16x8, dv), opnd[mm], dkacc[d]);
+                }
+            }
+        };
+        auto ds_pair = [&](auto qc) {  // pair q in 0..7, in the order the dV / dK products consume them
+            constexpr int q = decltype(qc)::value;
+            constexpr int step = q >> 2, i2 = (q & 3) * 2, e = step * 8 + i2, rg = e >> 2, el = e & 3;
+            float p0 = fast_exp2(fmaf(cur.s[e], c2, -l2[rg][el]));
+            float p1 = fast_exp2(fmaf(cur.s[e + 1], c2, -l2[rg][el + 1]));
+            if (MASK) {
+                const int rp0 = ps[rg][el], rp1 = ps[rg][el + 1];
+                bool ok0 = rp0 >= key && key < gm.T, ok1 = rp1 >= key && key < gm.T;
+                if (local) {
+                    ok0 = ok0 && (rp0 - key <= gm.W);
+                    ok1 = ok1 && (rp1 - key <= gm.W);
+                }
+                p0 = ok0 ? p0 : 0.f;
+                p1 = ok1 ? p1 : 0.f;
+            }
+            f32x2 fp = {p0, p1};
+            f32x2 fd = {p0 * (cur.dp[e] - dl[rg][el]), p1 * (cur.dp[e + 1] - dl[rg][el + 1])};
+            pw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fp, bf16x2));
+            dsw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fd, bf16x2));
+        };
+
+        static_for<0, kAhead>([&](auto mc) { read_operand(mc); });
+        L2A_FENCE();
+        static_for<0, 32>([&](auto mc) {
+            constexpr int mm = decltype(mc)::value;
+            issue(mc);
+            read_operand(Int<mm + kAhead>{});
+            static_for<0, 8>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                if constexpr ((q * 7) / 4 == mm) ds_pair(qc);
+            });
+            L2A_FENCE();
+        });
+    };
+
+    if (total > 0) {
+        // ---- prologue: row-major tiles 0 and 1, token-minor tile 0; S, dP of tile 0
+        SdP Xa, Xb;
+        load_rm(0, 0);
+        if (total > 1) load_rm(1, 1);
+        load_tm(0, 0);
+        dma_wait();
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            Xa.s = mfma32(rm_operand(lds_rm[0].q_rm, n, ks, h), kreg[ks], ks == 0 ? zero16 : Xa.s);
+            Xa.dp = mfma32(rm_operand(lds_rm[0].g_rm, n, ks, h), vreg[ks], ks == 0 ? zero16 : Xa.dp);
+        }
+
+        // two tiles per trip so that the two S/dP buffers swap roles without copies
+        auto one = [&](auto mask_tag, SdP& cur, SdP& nxt, int it, bool local) __attribute__((always_inline)) {
+            if (it + 2 < total) load_rm(it + 2, it & 1);        // that buffer held tile it: consumed one step ago
+            if (it + 1 < total) load_tm(it + 1, (it + 1) & 1);  // held tile it-1: consumed one step ago
+            tile_step(mask_tag, cur, nxt, lds_rm[(it + 1) & 1], lds_tm[it & 1], local);
+            dma_wait();
+            __syncthreads();
+        };
+        auto run = [&](auto mask_tag, int it_begin, int it_end, bool local) __attribute__((always_inline)) {
+            for (int it = it_begin; it < it_end; it += 2) {
+                one(mask_tag, Xa, Xb, it, local);
+                if (it + 1 < it_end) {
+                    one(mask_tag, Xb, Xa, it + 1, local);
+                } else {
+                    Xa.s = Xb.s;
+                    Xa.dp = Xb.dp;
+                }
+            }
+        };
+        for (int seg = 0; seg < 6; ++seg) {
+            const int s = seg / 3, part = seg - 3 * s;
+            if (s >= a.nsets) break;
+            const int sb = s ? tb1 : tb0, sh = s ? th1 : th0, st_ = s ? tt1 : tt0, se = s ? te1 : te0;
+            const int base = (s ? n0 : 0) - sb;  // flat index = base + tile
+            const int tb = part == 0 ? sb : (part == 1 ? sh : st_);
+            const int te = part == 0 ? sh : (part == 1 ? st_ : se);
+            if (tb >= te) continue;
+            const bool local = (s ? a.rs[1].local : a.rs[0].local) != 0;
+            if (part == 1)
+                run(std::false_type{}, base + tb, base + te, local);
+            else
+                run(std::true_type{}, base + tb, base + te, local);
+        }
+    }
+
+    // ---- write dK, dV: lane = channel d*32+n, register e = key c_row(e, h)
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int kk = kw0 + c_row(e, h);
+            if (kk < gm.T) {
+                const size_t off = (((size_t)b * gm.T + kk) * gm.Hkv + hk) * kD + d * 32 + n;
+                a.dk[off] = (__bf16)(dkacc[d][e] * gm.scale);
+                a.dv[off] = (__bf16)dvacc[d][e];
+            }
+        }
+}
+
+}  // namespace
+
+// packed[s]: compact copies of set s made by pack_rows (7 pointers in the order of PackedRows)
+int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[7], int cap,
+                  const void* k, const void* v, void* dk, void* dv, hipStream_t st) {
+    if (g.D != kD) return L2A_ERR_UNSUPPORTED;
+    DkdvArgs a{};
+    a.gm = g;
+    a.nsets = nsets;
+    a.cap = cap;
+    for (int i = 0; i < nsets; ++i) {
+        a.rs[i] = sets[i];
+        a.rows[i] = PackedRows{(const __bf16*)packed[i][0], (const __bf16*)packed[i][1], (const __bf16*)packed[i][2],
+                               (const __bf16*)packed[i][3], (const float*)packed[i][4], (const float*)packed[i][5],
+                               (const int32_t*)packed[i][6]};
+    }
+    a.k = (const __bf16*)k;
+    a.v = (const __bf16*)v;
+    a.dk = (__bf16*)dk;
+    a.dv = (__bf16*)dv;
+    const dim3 grid((g.T + kKeysPerWg - 1) / kKeysPerWg, g.B * g.Hkv);
+    KernelTimer kt("bwd_dkdv", st);
+    hipLaunchKernelGGL(bwd_dkdv_kernel, grid, dim3(kThreads), 0, st, a);
+    return launch_status();
+}
+
+}  // namespace l2a

@@ -91,8 +91,8 @@ int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, co
 int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* kt,
                 int kt_cap, const void* dO, const float* lse, float* delta, void* dq, int accumulate,
                 hipStream_t st);
-int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* q, const void* k, const void* v,
-                  const void* dO, const float* const* lse, const float* const* delta, void* dk, void* dv,
-                  hipStream_t st);
+// packed[s]: the seven outputs of pack_rows for set s (qc, gc, qt, gt, lse2_c, delta_c, pos_c)
+int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[7], int cap,
+                  const void* k, const void* v, void* dk, void* dv, hipStream_t st);
 
 }  // namespace l2a

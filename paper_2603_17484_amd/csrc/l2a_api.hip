@@ -52,17 +52,16 @@ size_t redo_bytes(const l2a_params& p) {
 size_t fwd_workspace_bytes(const l2a_params& p) { return use_mfma(p) ? 2 * kv_copy_bytes(p) + redo_bytes(p) : 0; }
 // backward: delta of each branch; matrix-core path: + token-minor copies of K (one per branch)
 size_t delta_bytes(const l2a_params& p) { return (sizeof(float) * stat_elems(p) + 255) / 256 * 256; }
+// compact copies of a branch's rows for the dK/dV kernel: Q, dO row-major and token-minor, + 3 statistics
+int rows_cap(const l2a_params& p) { return (int)(((long long)p.T * (p.Hq / p.Hkv) + 63) / 64 * 64); }
+size_t rows_copy_bytes(const l2a_params& p) { return (size_t)p.B * p.Hkv * rows_cap(p) * p.D * 2; }
+size_t rows_stat_bytes(const l2a_params& p) { return ((size_t)p.B * p.Hkv * rows_cap(p) * 4 + 255) / 256 * 256; }
+size_t packed_set_bytes(const l2a_params& p) { return 4 * rows_copy_bytes(p) + 3 * rows_stat_bytes(p); }
 size_t bwd_workspace_bytes(const l2a_params& p) {
-    return 2 * delta_bytes(p) + (use_mfma(p) ? 2 * kv_copy_bytes(p) : 0);
+    return 2 * delta_bytes(p) + (use_mfma(p) ? 2 * kv_copy_bytes(p) + 2 * packed_set_bytes(p) : 0);
 }
 
 
-int bwd_dkdv(const l2a_params& p, const Geom& g, const RowSet* sets, int n, const void* q, const void* k,
-             const void* v, const void* dO, const float* const* lse, const float* const* delta, void* dk, void* dv,
-             hipStream_t st) {
-    return use_mfma(p) ? mfma_bwd_dkdv(g, sets, n, q, k, v, dO, lse, delta, dk, dv, st)
-                       : simple_bwd_dkdv(g, p.dtype, sets, n, q, k, v, dO, lse, delta, dk, dv, st);
-}
 
 }  // namespace
 
@@ -235,24 +234,45 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
         if ((r = bwd_dq(rs_g, q_glb, k_glb, v_glb, kt_glb, lse_global, delta_g, dq_glb, out_alias ? 1 : 0)) != L2A_OK)
             return r;
     }
-    // dK, dV: one pass over the key tokens; with shared inputs both branches accumulate in registers
+    // dK, dV: one pass over the key tokens; with shared inputs both branches accumulate in registers.
+    // The matrix-core kernel reads each branch's rows from compact copies (layout pre-pass).
+    char* packed_base = (char*)workspace + 2 * delta_bytes(*p) + 2 * kv_copy_bytes(*p);
+    const int cap = rows_cap(*p);
+    auto dkdv = [&](const RowSet* sets, int n, const void* const* qs, const float* const* lses,
+                    const float* const* deltas, const void* k, const void* v, void* dk, void* dv) -> int {
+        if (!mfma) return simple_bwd_dkdv(g, p->dtype, sets, n, qs[0], k, v, dO, lses, deltas, dk, dv, st);
+        const void* packed[2][7];
+        for (int i = 0; i < n; ++i) {
+            char* base = packed_base + (sets[i].local ? 0 : packed_set_bytes(*p));
+            char* stat = base + 4 * rows_copy_bytes(*p);
+            void* out[7] = {base, base + rows_copy_bytes(*p), base + 2 * rows_copy_bytes(*p),
+                            base + 3 * rows_copy_bytes(*p), stat, stat + rows_stat_bytes(*p),
+                            stat + 2 * rows_stat_bytes(*p)};
+            const int rc2 = pack_rows(g, sets[i], qs[i], dO, lses[i], deltas[i], out[0], out[1], out[2], out[3],
+                                      (float*)out[4], (float*)out[5], (int32_t*)out[6], cap, st);
+            if (rc2 != L2A_OK) return rc2;
+            for (int j = 0; j < 7; ++j) packed[i][j] = out[j];
+        }
+        return mfma_bwd_dkdv(g, sets, n, packed, cap, k, v, dk, dv, st);
+    };
     if (out_alias) {
         const RowSet sets[2] = {rs_l, rs_g};
+        const void* qs[2] = {q_loc, q_loc};
         const float* lses[2] = {lse_local, lse_global};
         const float* deltas[2] = {delta_l, delta_g};
-        return bwd_dkdv(*p, g, sets, 2, q_loc, k_loc, v_loc, dO, lses, deltas, dk_loc, dv_loc, st);
+        return dkdv(sets, 2, qs, lses, deltas, k_loc, v_loc, dk_loc, dv_loc);
     }
     if (do_local) {
+        const void* qs[1] = {q_loc};
         const float* lses[1] = {lse_local};
         const float* deltas[1] = {delta_l};
-        if ((r = bwd_dkdv(*p, g, &rs_l, 1, q_loc, k_loc, v_loc, dO, lses, deltas, dk_loc, dv_loc, st)) != L2A_OK)
-            return r;
+        if ((r = dkdv(&rs_l, 1, qs, lses, deltas, k_loc, v_loc, dk_loc, dv_loc)) != L2A_OK) return r;
     }
     if (do_global) {
+        const void* qs[1] = {q_glb};
         const float* lses[1] = {lse_global};
         const float* deltas[1] = {delta_g};
-        if ((r = bwd_dkdv(*p, g, &rs_g, 1, q_glb, k_glb, v_glb, dO, lses, deltas, dk_glb, dv_glb, st)) != L2A_OK)
-            return r;
+        if ((r = dkdv(&rs_g, 1, qs, lses, deltas, k_glb, v_glb, dk_glb, dv_glb)) != L2A_OK) return r;
     }
     return L2A_OK;
 }
