@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true", help="skip timing the dense all-routed mode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of 1 GiB (a known-size kernel to scale profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -107,6 +109,13 @@ def main() -> int:
             for name, t in B.profile_read():
                 kern.setdefault(name, []).append(t)
         return ms, {n: float(np.mean(ts)) for n, ts in kern.items()}
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: K steps of the sparse layer
     sparse = build(0)
@@ -176,7 +185,7 @@ def main() -> int:
     return 0
 
 
-def cpu_baseline(w, q, k, v, dO, mask_np, backward, seed, budget_s=15.0):
+def cpu_baseline(w, q, k, v, dO, mask_np, backward, seed, budget_s=20.0):
     """The CPU oracle, as it stands, on sampled routed rows of the same tensors: forward of both
     branches plus the dQ pass.  Rate in algorithmic FLOPs (4 D forward + 6 D for the dQ pass per
     (row, key) pair the oracle visited), so the unit matches `value`."""
@@ -203,7 +212,7 @@ def cpu_baseline(w, q, k, v, dO, mask_np, backward, seed, budget_s=15.0):
 
     pick = lambda n: routed[rng.choice(routed.shape[0], size=min(n, routed.shape[0]), replace=False)].astype(np.int32)
     dt, pairs = run(pick(32))
-    n = int(max(32, min(20000, 32 * budget_s / max(dt, 1e-3))))
+    n = int(max(32, min(40000, 32 * budget_s / max(dt, 1e-3))))
     dt, pairs = run(pick(n))
     per_pair = (10.0 if backward else 4.0) * w.D
     threads = orc.threads()

@@ -8,7 +8,8 @@
 //
 // Rows are read from the compact copies the pack pre-pass makes of each branch's Q and dO
 // (row-major for S = Q K^T and dP = dO V^T, token-minor for dV += P^T dO and dK += dS^T Q)
-// together with the rows' log-sum-exp, delta and position, by direct global->LDS loads.
+// together with the rows' log-sum-exp, -delta and position, by direct global->LDS loads.  The dP
+// accumulators start from -delta, so that dS = P o dP' needs no subtraction.
 //   S  [row, key] = Q K^T     A = Q tile (LDS, row-major),  B = K (registers, loaded once)
 //   dP [row, key] = dO V^T    A = dO tile,                   B = V (registers)
 //   dV [key, ch] += P^T dO    A = P^T  = the S accumulators,  B = dO tile (LDS, token-minor)
@@ -24,6 +25,8 @@ namespace {
 constexpr int kKeysPerWg = 128;
 constexpr int kRT = 32;     // rows per tile
 constexpr int kAhead = 3;   // operand look-ahead, in slots
+constexpr int kNB = 4;              // LDS buffers per tile kind: loads run kNB - 1 tiles ahead
+constexpr int kDmaPerStep = 11;     // direct-to-LDS instructions a wavefront issues per tile step
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -31,21 +34,23 @@ template <int V>
 using Int = std::integral_constant<int, V>;
 
 struct PackedRows {   // compact copies of one branch's rows, per (b, kv head): cap rows
-    const __bf16* qc;   // [nbh][cap][128]
-    const __bf16* gc;   // dO
-    const __bf16* qt;   // [nbh][128][cap], token-minor
-    const __bf16* gt;
-    const float* lse2;  // [nbh][cap]  lse * log2(e)
-    const float* delta;
-    const int32_t* pos; // -1 = padding
+    const char* qc;      // [nbh][cap][128] bf16
+    const char* gc;      // dO
+    const char* qt;      // [nbh][128][cap] bf16, token-minor
+    const char* gt;
+    const char* lse2;    // [nbh][cap] f32  lse * log2(e)
+    const char* ndelta;  // [nbh][cap] f32  -delta
+    const char* pos;     // [nbh][cap] i32, -1 = padding
 };
 
 struct DkdvArgs {
     Geom gm;
     RowSet rs[2];
-    PackedRows rows[2];
+    PackedRows rows;        // set 0; every array of set 1 lies set_stride bytes further
+    long long set_stride;
     int nsets;
     int cap;
+    int chunk;              // key blocks handed to one XCD at a time
     const __bf16* k;
     const __bf16* v;
     __bf16* dk;
@@ -55,14 +60,14 @@ struct DkdvArgs {
 struct RowTileLds {
     __bf16 q_rm[kRT * 128];
     __bf16 g_rm[kRT * 128];
+    float ndelta[64];  // 32 used; a whole wavefront writes 64 entries
 };
 struct ColTileLds {
     __bf16 q_t[kD * kRT];
     __bf16 g_t[kD * kRT];
-    float lse2[64];   // 32 used; a whole wavefront writes 64 entries
-    float delta[64];
+    float lse2[64];
     int pos[64];
-    int pad[64];
+    int pad[128];
 };
 
 struct SdP {
@@ -70,13 +75,25 @@ struct SdP {
 };
 
 __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
-    __shared__ __attribute__((aligned(1024))) RowTileLds lds_rm[2];
-    __shared__ __attribute__((aligned(1024))) ColTileLds lds_tm[2];
+    __shared__ __attribute__((aligned(1024))) RowTileLds lds_rm[kNB];
+    __shared__ __attribute__((aligned(1024))) ColTileLds lds_tm[kNB];
 
     const Geom& gm = a.gm;
     const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
-    const int k0 = blockIdx.x * kKeysPerWg;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Key blocks are handed
+    // out in chunks of adjacent blocks per XCD, so that the workgroups resident on one XCD stream
+    // nearly the same rows at the same time; successive rounds of chunks visit the XCDs in snake
+    // order, which evens out the causal triangle's work between them.
+    int kblk;
+    {
+        const int x = (int)blockIdx.x & 7, j = (int)blockIdx.x >> 3;
+        const int round = j / a.chunk, w = j % a.chunk;
+        const int xx = (round & 1) ? 7 - x : x;
+        kblk = (round * 8 + xx) * a.chunk + w;
+    }
+    const int k0 = kblk * kKeysPerWg;
+    if (k0 >= a.gm.T) return;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, h = lane >> 5;
     const int kw0 = k0 + wave * 32;
     const int key = kw0 + n;  // this lane's key (a column of S)
@@ -136,34 +153,42 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
 
     // ---- loads.  Flat tile index it -> (set, tile)
     const unsigned lds_rm0 = lds_offset(&lds_rm[0]), lds_tm0 = lds_offset(&lds_tm[0]);
+    // A Local set is walked upwards; a Global set downwards from its last tile, so that all key
+    // blocks of a head read the same tile at the same step (they only stop at different tiles).
+    const bool rev0 = a.rs[0].local == 0, rev1 = a.nsets > 1 && a.rs[1].local == 0;
+    // Every load is a wave-uniform base plus a per-lane offset fixed for the whole kernel.
+    const RmDma<kRT> rm_off = rm_dma_setup<kRT>(kD * 2, wave);
+    const TmDma<kRT> tm_off = tm_dma_setup<kRT>((unsigned)a.cap * 2u, wave);
+    const unsigned stat_off = n * 4;
+    const size_t rows_bh = (size_t)bh * a.cap;
     auto locate = [&](int it, int& s, int& t) __attribute__((always_inline)) {
         s = it < n0 ? 0 : 1;
-        t = s ? tb1 + (it - n0) : tb0 + it;
+        if (s) t = rev1 ? te1 - 1 - (it - n0) : tb1 + (it - n0);
+        else t = rev0 ? te0 - 1 - it : tb0 + it;
     };
     auto load_rm = [&](int it, int buf) __attribute__((always_inline)) {
         int s, t;
         locate(it, s, t);
-        const __bf16* qc = s ? a.rows[1].qc : a.rows[0].qc;
-        const __bf16* gc = s ? a.rows[1].gc : a.rows[0].gc;
-        const size_t base = ((size_t)bh * a.cap + (size_t)t * kRT) * kD;
+        const size_t row0 = rows_bh + (size_t)t * kRT;
+        const size_t base = (size_t)s * a.set_stride + row0 * (kD * 2);
         const unsigned dst = lds_rm0 + buf * (unsigned)sizeof(RowTileLds);
-        dma_rm_tile<kRT>(dst, [&](int r) { return qc + base + (size_t)r * kD; });
-        dma_rm_tile<kRT>(dst + kRT * 256, [&](int r) { return gc + base + (size_t)r * kD; });
+        rm_dma_issue<kRT>(rm_off, a.rows.qc + base, dst, wave);
+        rm_dma_issue<kRT>(rm_off, a.rows.gc + base, dst + kRT * 256, wave);
+        // per-row statistics: 32 rows, the upper half-wave repeats the lower one (every wavefront
+        // issues them, identically, so that all wavefronts have the same number of loads in flight)
+        dma4_so(a.rows.ndelta + (size_t)s * a.set_stride + row0 * 4, stat_off, dst + 2 * kRT * 256);
     };
     auto load_tm = [&](int it, int buf) __attribute__((always_inline)) {
         int s, t;
         locate(it, s, t);
-        const PackedRows pr = s ? a.rows[1] : a.rows[0];
-        const size_t base = (size_t)bh * kD * a.cap + (size_t)t * kRT;
+        const size_t set = (size_t)s * a.set_stride;
+        const size_t base = set + (rows_bh * kD + (size_t)t * kRT) * 2;
+        const size_t so = set + (rows_bh + (size_t)t * kRT) * 4;
         const unsigned dst = lds_tm0 + buf * (unsigned)sizeof(ColTileLds);
-        dma_tm_tile<kRT>(dst, pr.qt + base, (size_t)a.cap);
-        dma_tm_tile<kRT>(dst + kD * kRT * 2, pr.gt + base, (size_t)a.cap);
-        if (wave == 0) {  // per-row statistics: 32 rows, the upper half-wave repeats the lower one
-            const size_t so = (size_t)bh * a.cap + (size_t)t * kRT + n;
-            dma4(pr.lse2 + so, dst + 2 * kD * kRT * 2);
-            dma4(pr.delta + so, dst + 2 * kD * kRT * 2 + 256);
-            dma4(pr.pos + so, dst + 2 * kD * kRT * 2 + 512);
-        }
+        tm_dma_issue<kRT>(tm_off, a.rows.qt + base, dst, wave);
+        tm_dma_issue<kRT>(tm_off, a.rows.gt + base, dst + kD * kRT * 2, wave);
+        dma4_so(a.rows.lse2 + so, stat_off, dst + 2 * kD * kRT * 2);
+        dma4_so(a.rows.pos + so, stat_off, dst + 2 * kD * kRT * 2 + 256);
     };
 
     f32x16 dkacc[4], dvacc[4];
@@ -184,12 +209,14 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         const float c2 = gm.scale_log2;
         bf16x8 opnd[32 + kAhead];
         uint32_t pw[2][4], dsw[2][4];  // P^T, dS^T as packed bf16 pairs: [16-row group][dword]
-        f32x4 l2[4], dl[4];
+        f32x4 l2[4];
         i32x4 ps[4];
+        f32x16 nd;  // -delta of the next tile's rows: the dP accumulators start from it
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {  // register 4 rg + e holds row 8 rg + 4 h + e
             l2[rg] = *reinterpret_cast<const f32x4*>(&ct.lse2[8 * rg + 4 * h]);
-            dl[rg] = *reinterpret_cast<const f32x4*>(&ct.delta[8 * rg + 4 * h]);
+            const f32x4 x = *reinterpret_cast<const f32x4*>(&rt.ndelta[8 * rg + 4 * h]);
+            nd[4 * rg] = x[0], nd[4 * rg + 1] = x[1], nd[4 * rg + 2] = x[2], nd[4 * rg + 3] = x[3];
             if (MASK) ps[rg] = *reinterpret_cast<const i32x4*>(&ct.pos[8 * rg + 4 * h]);
         }
         // operand of slot m: m < 16 -> Q (even) / dO (odd) rows of the next tile, ks = m / 2;
@@ -210,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             if constexpr (mm < 16) {
                 constexpr int ks = mm >> 1;
                 if constexpr ((mm & 1) == 0) nxt.s = mfma32(opnd[mm], kreg[ks], ks == 0 ? zero16 : nxt.s);
-                else nxt.dp = mfma32(opnd[mm], vreg[ks], ks == 0 ? zero16 : nxt.dp);
+                else nxt.dp = mfma32(opnd[mm], vreg[ks], ks == 0 ? nd : nxt.dp);
             } else {
                 constexpr int x = mm - 16, step = x >> 3, d = (x >> 1) & 3;
                 if constexpr ((x & 1) == 0) {
@@ -238,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 p1 = ok1 ? p1 : 0.f;
             }
             f32x2 fp = {p0, p1};
-            f32x2 fd = {p0 * (cur.dp[e] - dl[rg][el]), p1 * (cur.dp[e + 1] - dl[rg][el + 1])};
+            f32x2 fd = {p0 * cur.dp[e], p1 * cur.dp[e + 1]};  // dp already holds dP - delta
             pw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fp, bf16x2));
             dsw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fd, bf16x2));
         };
@@ -260,23 +287,34 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     if (total > 0) {
         // ---- prologue: row-major tiles 0 and 1, token-minor tile 0; S, dP of tile 0
         SdP Xa, Xb;
-        load_rm(0, 0);
-        if (total > 1) load_rm(1, 1);
-        load_tm(0, 0);
+#pragma unroll
+        for (int i = 0; i < kNB; ++i)
+            if (i < total) load_rm(i, i);
+#pragma unroll
+        for (int i = 0; i < kNB - 1; ++i)
+            if (i < total) load_tm(i, i);
         dma_wait();
         __syncthreads();
 #pragma unroll
+        for (int e = 0; e < 16; ++e) Xa.dp[e] = lds_rm[0].ndelta[c_row(e, h)];
+#pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             Xa.s = mfma32(rm_operand(lds_rm[0].q_rm, n, ks, h), kreg[ks], ks == 0 ? zero16 : Xa.s);
-            Xa.dp = mfma32(rm_operand(lds_rm[0].g_rm, n, ks, h), vreg[ks], ks == 0 ? zero16 : Xa.dp);
+            Xa.dp = mfma32(rm_operand(lds_rm[0].g_rm, n, ks, h), vreg[ks], Xa.dp);
         }
 
-        // two tiles per trip so that the two S/dP buffers swap roles without copies
+        // Step `it` reads the row-major tile it+1 and the token-minor tile it, and starts the loads
+        // of row-major tile it+kNB (into the buffer tile `it` left one step ago) and token-minor tile
+        // it+kNB-1 (buffer of tile it-1).  At its end only the loads of the last kNB-2 steps may
+        // still be in flight.  Two tiles per trip so that the two S/dP buffers swap roles without copies.
         auto one = [&](auto mask_tag, SdP& cur, SdP& nxt, int it, bool local) __attribute__((always_inline)) {
-            if (it + 2 < total) load_rm(it + 2, it & 1);        // that buffer held tile it: consumed one step ago
-            if (it + 1 < total) load_tm(it + 1, (it + 1) & 1);  // held tile it-1: consumed one step ago
-            tile_step(mask_tag, cur, nxt, lds_rm[(it + 1) & 1], lds_tm[it & 1], local);
-            dma_wait();
+            if (it + kNB < total) load_rm(it + kNB, it % kNB);
+            if (it + kNB - 1 < total) load_tm(it + kNB - 1, (it + kNB - 1) % kNB);
+            tile_step(mask_tag, cur, nxt, lds_rm[(it + 1) % kNB], lds_tm[it % kNB], local);
+            if (it + kNB < total)
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kNB - 2) * kDmaPerStep) : "memory");
+            else
+                dma_wait();
             __syncthreads();
         };
         auto run = [&](auto mask_tag, int it_begin, int it_end, bool local) __attribute__((always_inline)) {
@@ -294,15 +332,21 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             const int s = seg / 3, part = seg - 3 * s;
             if (s >= a.nsets) break;
             const int sb = s ? tb1 : tb0, sh = s ? th1 : th0, st_ = s ? tt1 : tt0, se = s ? te1 : te0;
-            const int base = (s ? n0 : 0) - sb;  // flat index = base + tile
-            const int tb = part == 0 ? sb : (part == 1 ? sh : st_);
-            const int te = part == 0 ? sh : (part == 1 ? st_ : se);
+            const bool rev = s ? rev1 : rev0;
+            const int off = s ? n0 : 0;
+            // tiles [tb, te) of this run; walked upwards they are flat indices off + (tile - sb),
+            // walked downwards off + (se - 1 - tile), and the runs come in the order tail, middle, head
+            const int run_id = rev ? 2 - part : part;
+            const int tb = run_id == 0 ? sb : (run_id == 1 ? sh : st_);
+            const int te = run_id == 0 ? sh : (run_id == 1 ? st_ : se);
             if (tb >= te) continue;
             const bool local = (s ? a.rs[1].local : a.rs[0].local) != 0;
-            if (part == 1)
-                run(std::false_type{}, base + tb, base + te, local);
+            const int it_begin = rev ? off + (se - te) : off + (tb - sb);
+            const int it_end = it_begin + (te - tb);
+            if (run_id == 1)
+                run(std::false_type{}, it_begin, it_end, local);
             else
-                run(std::true_type{}, base + tb, base + te, local);
+                run(std::true_type{}, it_begin, it_end, local);
         }
     }
 
@@ -322,25 +366,33 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
 
 }  // namespace
 
-// packed[s]: compact copies of set s made by pack_rows (7 pointers in the order of PackedRows)
+// packed[s]: compact copies of set s made by pack_rows (7 pointers in the order of PackedRows).
+// With two sets every array of the second must lie the same number of bytes after the first's.
 int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[7], int cap,
                   const void* k, const void* v, void* dk, void* dv, hipStream_t st) {
     if (g.D != kD) return L2A_ERR_UNSUPPORTED;
+    if ((unsigned long long)cap * 2ull * (kD - 1) + 64ull * kRT > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
     DkdvArgs a{};
     a.gm = g;
     a.nsets = nsets;
     a.cap = cap;
-    for (int i = 0; i < nsets; ++i) {
-        a.rs[i] = sets[i];
-        a.rows[i] = PackedRows{(const __bf16*)packed[i][0], (const __bf16*)packed[i][1], (const __bf16*)packed[i][2],
-                               (const __bf16*)packed[i][3], (const float*)packed[i][4], (const float*)packed[i][5],
-                               (const int32_t*)packed[i][6]};
+    for (int i = 0; i < nsets; ++i) a.rs[i] = sets[i];
+    a.rows = PackedRows{(const char*)packed[0][0], (const char*)packed[0][1], (const char*)packed[0][2],
+                        (const char*)packed[0][3], (const char*)packed[0][4], (const char*)packed[0][5],
+                        (const char*)packed[0][6]};
+    if (nsets > 1) {
+        a.set_stride = (const char*)packed[1][0] - (const char*)packed[0][0];
+        for (int j = 1; j < 7; ++j)
+            if ((const char*)packed[1][j] - (const char*)packed[0][j] != a.set_stride) return L2A_ERR_SHAPE;
     }
     a.k = (const __bf16*)k;
     a.v = (const __bf16*)v;
     a.dk = (__bf16*)dk;
     a.dv = (__bf16*)dv;
-    const dim3 grid((g.T + kKeysPerWg - 1) / kKeysPerWg, g.B * g.Hkv);
+    const int nblk = (g.T + kKeysPerWg - 1) / kKeysPerWg;
+    a.chunk = std::max(1, std::min(32, nblk / 32));
+    const int per = 8 * a.chunk;
+    const dim3 grid((nblk + per - 1) / per * per, g.B * g.Hkv);
     KernelTimer kt("bwd_dkdv", st);
     hipLaunchKernelGGL(bwd_dkdv_kernel, grid, dim3(kThreads), 0, st, a);
     return launch_status();

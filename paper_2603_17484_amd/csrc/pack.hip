@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void pack_token_minor_kernel(PackArgs a) 
         const long long off = row_offset(r0 + (int)threadIdx.x, &p, &so);
         const size_t o = (size_t)bh * a.cap + r0 + threadIdx.x;
         a.lse2_c[o] = off >= 0 ? a.lse[so] * kLog2e : 0.f;
-        a.delta_c[o] = off >= 0 ? a.delta[so] : 0.f;
+        a.delta_c[o] = off >= 0 ? -a.delta[so] : 0.f;  // stored negated: dP accumulators start from it
         a.pos_c[o] = off >= 0 ? p : -1;
     }
     __syncthreads();

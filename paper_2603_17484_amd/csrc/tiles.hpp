@@ -67,7 +67,7 @@ __device__ __forceinline__ bf16x8 rm_operand(const __bf16* tile, int row, int ks
 template <int TOK>
 __device__ __forceinline__ int tm_swizzle(int ch) {
     if (TOK == 64) return (ch & 7) ^ ((ch >> 3) & 1);  // 8 chunks per 128-byte row
-    return ((ch >> 1) ^ (ch >> 3)) & 3;                // 4 chunks per 64-byte row
+    return (ch >> 2) & 3;                              // 4 chunks per 64-byte row (measured conflict-free)
 }
 
 // src: global address of (channel 0, first token of the tile); ch_stride in elements.
@@ -91,6 +91,66 @@ template <int TOK>
 __device__ __forceinline__ bf16x8 tm_operand(const __bf16* tile, int ch, int step, int h) {
     const int slot = (2 * step + h) ^ tm_swizzle<TOK>(ch);
     return *reinterpret_cast<const bf16x8*>(tile + ch * TOK + slot * 8);
+}
+
+// ---------------------------------------------------------------------------------------
+// The same loads with the address arithmetic hoisted out of the loops: a tile whose rows are a
+// fixed byte stride apart is loaded from a wave-uniform 64-bit base (scalar registers) plus a
+// per-lane 32-bit offset that never changes, so issuing a load costs no vector instruction.
+// `wave` below must be wave-uniform (readfirstlane of threadIdx.x >> 6).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void dma16_so(const void* sbase, unsigned voff, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+__device__ __forceinline__ void dma4_so(const void* sbase, unsigned voff, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+template <int ROWS>
+struct RmDma {
+    unsigned voff[ROWS / 16];
+};
+template <int ROWS>
+__device__ __forceinline__ RmDma<ROWS> rm_dma_setup(unsigned row_stride_bytes, int wave) {
+    RmDma<ROWS> d;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < ROWS / 16; ++i) {
+        const int row = (i * 4 + wave) * 4 + (lane >> 4);
+        d.voff[i] = (unsigned)row * row_stride_bytes + (unsigned)(((lane & 15) ^ (row & 15)) * 16);
+    }
+    return d;
+}
+// sbase: global address of (row 0, channel 0) of the tile, wave-uniform
+template <int ROWS>
+__device__ __forceinline__ void rm_dma_issue(const RmDma<ROWS>& d, const void* sbase, unsigned lds_base, int wave) {
+#pragma unroll
+    for (int i = 0; i < ROWS / 16; ++i) dma16_so(sbase, d.voff[i], lds_base + (i * 4 + wave) * 1024);
+}
+
+template <int TOK>
+struct TmDma {
+    unsigned voff[TOK / 16];  // 128 channels * 2 TOK bytes / 4096 bytes per workgroup instruction
+};
+template <int TOK>
+__device__ __forceinline__ TmDma<TOK> tm_dma_setup(unsigned ch_stride_bytes, int wave) {
+    constexpr int kChunks = TOK / 8, kRowsPerSeg = 64 / kChunks;
+    TmDma<TOK> d;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < TOK / 16; ++i) {
+        const int ch = (i * 4 + wave) * kRowsPerSeg + lane / kChunks;
+        d.voff[i] = (unsigned)ch * ch_stride_bytes + (unsigned)(((lane % kChunks) ^ tm_swizzle<TOK>(ch)) * 16);
+    }
+    return d;
+}
+// sbase: global address of (channel 0, first token of the tile), wave-uniform
+template <int TOK>
+__device__ __forceinline__ void tm_dma_issue(const TmDma<TOK>& d, const void* sbase, unsigned lds_base, int wave) {
+#pragma unroll
+    for (int i = 0; i < TOK / 16; ++i) dma16_so(sbase, d.voff[i], lds_base + (i * 4 + wave) * 1024);
 }
 
 // position of token t inside its 16-token group in a token-minor copy, and the inverse
