@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     if ((int)blockIdx.x >= n_tiles) return;
     const int tile = n_tiles - 1 - (int)blockIdx.x;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, h = lane >> 5;
 
     const int wg_r0 = tile * kBQ;
@@ -96,21 +96,29 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     if (LOCAL) j_mid = min(jb1 + 1, max(jb0, (max(wg_pmax - gm.W, 0) + kBK - 1) / kBK));
     const int j_diag = max(j_mid, min(jb1 + 1, (wg_pmin + 1) / kBK));
 
-    const size_t kv_row = (size_t)gm.Hkv * kD;
-    const __bf16* kbase = a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
-    const __bf16* vbase = a.v + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
-    const __bf16* ktbase = a.kt + (size_t)bh * kD * a.kt_cap;
+    // Loads: a wave-uniform base per block plus per-lane offsets fixed for the whole kernel.
+    const unsigned kv_row_bytes = (unsigned)gm.Hkv * kD * 2;
+    const size_t kv_head = ((size_t)b * gm.T * gm.Hkv + hk) * kD;
+    const char* kbase = (const char*)(a.k + kv_head);
+    const char* vbase = (const char*)(a.v + kv_head);
+    const char* ktbase = (const char*)(a.kt + (size_t)bh * kD * a.kt_cap);
     const unsigned lds_k0 = lds_offset(&lds_k[0][0]), lds_v0 = lds_offset(&lds_v[0][0]);
     const unsigned lds_kt0 = lds_offset(&lds_kt[0][0]);
+    const RmDma<kBK> kv_off = rm_dma_setup<kBK>(kv_row_bytes, wave);
+    const TmDma<kBK> kt_off = tm_dma_setup<kBK>((unsigned)a.kt_cap * 2u, wave);
     auto load_kv = [&](int jb, int buf) __attribute__((always_inline)) {
-        // keys past the end of the sequence are clamped: always masked, never out of bounds
-        dma_rm_tile<kBK>(lds_k0 + buf * (kBK * 256),
-                         [&](int rr) { return kbase + (size_t)min(jb * kBK + rr, gm.T - 1) * kv_row; });
-        dma_rm_tile<kBK>(lds_v0 + buf * (kBK * 256),
-                         [&](int rr) { return vbase + (size_t)min(jb * kBK + rr, gm.T - 1) * kv_row; });
+        const size_t src = (size_t)jb * kBK * kv_row_bytes;
+        const unsigned dk_ = lds_k0 + buf * (kBK * 256), dv_ = lds_v0 + buf * (kBK * 256);
+        if ((jb + 1) * kBK <= gm.T) {
+            rm_dma_issue<kBK>(kv_off, kbase + src, dk_, wave);
+            rm_dma_issue<kBK>(kv_off, vbase + src, dv_, wave);
+        } else {  // keys past the end of the sequence are clamped: always masked, never out of bounds
+            rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, kbase + src, dk_, wave);
+            rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, vbase + src, dv_, wave);
+        }
     };
     auto load_kt = [&](int jb, int buf) __attribute__((always_inline)) {
-        dma_tm_tile<kBK>(lds_kt0 + buf * (kD * kBK * 2), ktbase + (size_t)jb * kBK, (size_t)a.kt_cap);
+        tm_dma_issue<kBK>(kt_off, ktbase + (size_t)jb * kBK * 2, lds_kt0 + buf * (kD * kBK * 2), wave);
     };
 
     f32x16 acc[4];
@@ -254,6 +262,8 @@ int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, c
                 int kt_cap, const void* dO, const float* lse, float* delta, void* dq, int accumulate,
                 hipStream_t st) {
     if (g.D != kD) return L2A_ERR_UNSUPPORTED;
+    // per-lane load offsets are 32-bit
+    if ((unsigned long long)kt_cap * 2ull * kD > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
     DqArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)kt, kt_cap,
              (const __bf16*)dO, lse, delta, (__bf16*)dq, accumulate};
     const long long rows = (long long)g.T * g.G;

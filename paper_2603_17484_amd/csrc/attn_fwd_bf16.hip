@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     if ((int)blockIdx.x >= n_tiles) return;
     const int tile = n_tiles - 1 - (int)blockIdx.x;  // longest prefixes first
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, h = lane >> 5;
 
     // ---- rows of this workgroup / wavefront / lane
@@ -101,17 +101,22 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     if (LOCAL) j_mid = min(jb1 + 1, max(jb0, (max(wg_pmax - gm.W, 0) + kBK - 1) / kBK));
     const int j_diag = max(j_mid, min(jb1 + 1, (wg_pmin + 1) / kBK));  // first block with a key > some row
 
-    const size_t kv_row = (size_t)gm.Hkv * kD;
-    const __bf16* kbase = a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD;
-    const __bf16* vtbase = a.vt + (size_t)bh * kD * a.vt_cap;
+    // Loads: a wave-uniform base per block plus per-lane offsets fixed for the whole kernel.
+    const unsigned kv_row_bytes = (unsigned)gm.Hkv * kD * 2;
+    const char* kbase = (const char*)(a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD);
+    const char* vtbase = (const char*)(a.vt + (size_t)bh * kD * a.vt_cap);
     const unsigned lds_k0 = lds_offset(&lds_k[0][0]), lds_v0 = lds_offset(&lds_v[0][0]);
+    const RmDma<kBK> k_off = rm_dma_setup<kBK>(kv_row_bytes, wave);
+    const TmDma<kBK> v_off = tm_dma_setup<kBK>((unsigned)a.vt_cap * 2u, wave);
     auto load_k = [&](int jb, int buf) __attribute__((always_inline)) {
-        // keys past the end of the sequence are clamped: always masked, never out of bounds
-        dma_rm_tile<kBK>(lds_k0 + buf * (kBK * 256),
-                         [&](int r) { return kbase + (size_t)min(jb * kBK + r, gm.T - 1) * kv_row; });
+        const char* src = kbase + (size_t)jb * kBK * kv_row_bytes;
+        const unsigned dst = lds_k0 + buf * (kBK * 256);
+        if ((jb + 1) * kBK <= gm.T) rm_dma_issue<kBK>(k_off, src, dst, wave);
+        else  // keys past the end of the sequence are clamped: always masked, never out of bounds
+            rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, src, dst, wave);
     };
     auto load_v = [&](int jb, int buf) __attribute__((always_inline)) {
-        dma_tm_tile<kBK>(lds_v0 + buf * (kD * kBK * 2), vtbase + (size_t)jb * kBK, (size_t)a.vt_cap);
+        tm_dma_issue<kBK>(v_off, vtbase + (size_t)jb * kBK * 2, lds_v0 + buf * (kD * kBK * 2), wave);
     };
 
     f32x16 oacc[4][kNQB];
@@ -556,6 +561,8 @@ __global__ __launch_bounds__(kThreads) void fwd_fixup_kernel(FwdArgs a) {
 int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* vt,
              int vt_cap, int32_t* redo, const FwdOut& out, hipStream_t st) {
     if (g.D != kD) return L2A_ERR_UNSUPPORTED;
+    // per-lane load offsets are 32-bit
+    if ((unsigned long long)vt_cap * 2ull * kD > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
     FwdArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)vt, vt_cap, redo, out};
     const long long rows = (long long)g.T * g.G;
     const dim3 grid((unsigned)((rows + kBQ - 1) / kBQ), g.B * g.Hkv);

@@ -23,37 +23,12 @@ __device__ __forceinline__ unsigned lds_offset(const void* p) {
     return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
-// 64 lanes x 16 bytes: lane l's 16 bytes at `gptr` -> LDS bytes [lds_base + 16 l, +16).
-// lds_base must be wave-uniform.  Completion is tracked by vmcnt (dma_wait).
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
-    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory");
-}
-// 64 lanes x 4 bytes
-__device__ __forceinline__ void dma4(const void* gptr, unsigned lds_base) {
-    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(base), "v"(gptr) : "memory");
-}
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---------------------------------------------------------------------------------------
 // Row-major tile: ROWS tokens x 128 channels, 256-byte rows, chunk c of row r in slot c ^ (r & 15).
 // ---------------------------------------------------------------------------------------
 constexpr int kRmRowBytes = 256;
-
-// row_ptr(r) -> global address of channel 0 of tile row r (must be valid for every r < ROWS).
-// Executed by all 256 threads of the workgroup.
-template <int ROWS, typename RowPtr>
-__device__ __forceinline__ void dma_rm_tile(unsigned lds_base, RowPtr row_ptr) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int i = 0; i < ROWS / 16; ++i) {
-        const int seg = i * 4 + wave;  // 1024-byte segment = 4 rows
-        const int row = seg * 4 + (lane >> 4);
-        const int c = (lane & 15) ^ (row & 15);
-        dma16(row_ptr(row) + c * 8, lds_base + seg * 1024);
-    }
-}
 
 // MFMA operand: row `row`, channels 16 ks + 8 h .. + 7
 __device__ __forceinline__ bf16x8 rm_operand(const __bf16* tile, int row, int ks, int h) {
@@ -70,22 +45,6 @@ __device__ __forceinline__ int tm_swizzle(int ch) {
     return (ch >> 2) & 3;                              // 4 chunks per 64-byte row (measured conflict-free)
 }
 
-// src: global address of (channel 0, first token of the tile); ch_stride in elements.
-template <int TOK>
-__device__ __forceinline__ void dma_tm_tile(unsigned lds_base, const __bf16* src, size_t ch_stride) {
-    constexpr int kChunks = TOK / 8;           // 16-byte chunks per row
-    constexpr int kRowsPerSeg = 64 / kChunks;  // rows per 1024-byte segment
-    constexpr int kSegs = 128 / kRowsPerSeg;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int i = 0; i < kSegs / 4; ++i) {
-        const int seg = i * 4 + wave;
-        const int ch = seg * kRowsPerSeg + lane / kChunks;
-        const int c = (lane % kChunks) ^ tm_swizzle<TOK>(ch);
-        dma16(src + (size_t)ch * ch_stride + c * 8, lds_base + seg * 1024);
-    }
-}
-
 // MFMA operand: channel `ch`, the eight tokens of 16-token group `step` that half-wave h contracts
 template <int TOK>
 __device__ __forceinline__ bf16x8 tm_operand(const __bf16* tile, int ch, int step, int h) {
@@ -94,10 +53,12 @@ __device__ __forceinline__ bf16x8 tm_operand(const __bf16* tile, int ch, int ste
 }
 
 // ---------------------------------------------------------------------------------------
-// The same loads with the address arithmetic hoisted out of the loops: a tile whose rows are a
-// fixed byte stride apart is loaded from a wave-uniform 64-bit base (scalar registers) plus a
-// per-lane 32-bit offset that never changes, so issuing a load costs no vector instruction.
-// `wave` below must be wave-uniform (readfirstlane of threadIdx.x >> 6).
+// Tile loads.  A tile whose rows are a fixed byte stride apart is loaded from a wave-uniform
+// 64-bit base (scalar registers) plus a per-lane 32-bit offset that never changes, so issuing a
+// load costs no vector instruction: lane l's 16 (or 4) bytes at sbase + voff go to LDS bytes
+// [lds_base + 16 l, +16) (or 4 l).  lds_base and `wave` (readfirstlane of threadIdx.x >> 6) must
+// be wave-uniform; offsets must stay below 4 GiB (checked by the host wrappers).  Completion is
+// tracked by vmcnt (dma_wait).
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void dma16_so(const void* sbase, unsigned voff, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
@@ -128,6 +89,21 @@ template <int ROWS>
 __device__ __forceinline__ void rm_dma_issue(const RmDma<ROWS>& d, const void* sbase, unsigned lds_base, int wave) {
 #pragma unroll
     for (int i = 0; i < ROWS / 16; ++i) dma16_so(sbase, d.voff[i], lds_base + (i * 4 + wave) * 1024);
+}
+
+// The same tile when only the first `rows_valid` rows exist in memory: later rows repeat the last
+// valid one (their contents never matter to the caller).  Per-lane arithmetic; for ragged ends only.
+template <int ROWS>
+__device__ __forceinline__ void rm_dma_issue_clamped(unsigned row_stride_bytes, int rows_valid, const void* sbase,
+                                                     unsigned lds_base, int wave) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < ROWS / 16; ++i) {
+        const int row = (i * 4 + wave) * 4 + (lane >> 4);
+        const unsigned voff =
+            (unsigned)min(row, rows_valid - 1) * row_stride_bytes + (unsigned)(((lane & 15) ^ (row & 15)) * 16);
+        dma16_so(sbase, voff, lds_base + (i * 4 + wave) * 1024);
+    }
 }
 
 template <int TOK>
