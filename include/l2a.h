@@ -73,7 +73,18 @@ typedef struct l2a_params {
 int l2a_version(void);
 const char* l2a_strerror(int code);
 
-/* Host-only, pure: scratch bytes each call needs (0 is possible; then workspace may be NULL). */
+/*
+ * Host-only, pure: scratch bytes each call needs (0 is possible; then workspace may be NULL).
+ * The workspace is device memory owned by the caller, 256-byte aligned, not preserved between
+ * calls; calls that share one workspace must be ordered on one stream.  What it holds:
+ *   route     one int32 count per (b, mask head, 2048-position chunk)
+ *   forward   bf16, D = 128 without L2A_FLAG_SCALAR: a token-minor copy [B,Hkv,D,ceil64(T)] of
+ *             each branch's V and one int32 flag per tile of 256 rows; else nothing
+ *   backward  delta_t of each branch, [B,Hq,T] float, twice; on the matrix-core path also a
+ *             token-minor copy of each branch's K and, per branch, compact copies of the rows'
+ *             Q and dO (row-major and token-minor, ceil64(T G) rows per (b, KV head)) with
+ *             three per-row statistics
+ */
 size_t l2a_route_workspace_bytes(const l2a_params* p);
 size_t l2a_attn_workspace_bytes(const l2a_params* p, int backward);
 

@@ -42,8 +42,19 @@ def test_params_struct_layout_matches_header():
 
 def test_workspace_queries(lib):
     p = B.make_params(1, 131072, 28, 4, 128, 4096, 28)
+    Bn, T, Hq, Hkv, D, G = 1, 131072, 28, 4, 128, 7
+    up = lambda x, m: (x + m - 1) // m * m
+    kv_copy = Bn * Hkv * D * up(T, 64) * 2            # token-minor copy of K or V, bf16
+    redo = up(4 * up(T * G, 256) // 256 * Bn * Hkv, 256)
+    delta = up(4 * Bn * Hq * T, 256)
+    cap = up(T * G, 64)
+    packed = 4 * (Bn * Hkv * cap * D * 2) + 3 * up(Bn * Hkv * cap * 4, 256)
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 0) == 2 * kv_copy + redo
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta + 2 * kv_copy + 2 * packed
+    p.flags = B.L2A_FLAG_SCALAR   # scalar kernels: only the two delta arrays
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 0) == 0
-    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * 4 * 28 * 131072
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta
+    p.flags = 0
     assert lib.l2a_route_workspace_bytes(ctypes.byref(p)) == 4 * 4 * (131072 // 2048)
     assert lib.l2a_kblk_entries(131072) == 2049 and lib.l2a_kblk_entries(65) == 3
     p.flags = B.L2A_FLAG_DENSE

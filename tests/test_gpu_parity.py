@@ -219,3 +219,122 @@ def test_bf16_scalar_kernels_agree(oracle):
 
 def test_bf16_custom_scale(oracle):
     run_and_check(oracle, make_case(T=300, Hq=4, Hkv=2, W=40, f=0.3, seed=31), scale=0.05)
+
+
+# ------------------------------------------------------------------------------------------
+# forward softmax reference: scores that grow along the sequence
+# ------------------------------------------------------------------------------------------
+def growing_scores_case(top, T=900, Hq=4, Hkv=2, W=200, seed=40):
+    """Keys whose score against every query grows linearly with the position up to `top` (natural
+    log units): the latest key dominates every row, far above the scores of a row's first blocks."""
+    x = make_case(T=T, Hq=Hq, Hkv=Hkv, W=W, f=0.5, seed=seed)
+    D = x.q.shape[-1]
+    x.q[...] = gen.round_to_bf16(1.0 + 0.05 * x.q)
+    ramp = (np.arange(T, dtype=np.float64) / T * top * np.sqrt(D) / D).astype(np.float32)
+    x.k[...] = gen.round_to_bf16(ramp[None, :, None, None] + 0.02 * x.k)
+    return x
+
+
+def redo_flags(lay):
+    """Flags of the tiles the pipelined forward kernel left to the fix-up kernel (last branch run):
+    they sit behind the two token-minor V copies in the forward workspace."""
+    p = lay.p
+    kv_copy = p.B * p.Hkv * p.D * ((p.T + 63) // 64 * 64) * 2
+    n = (p.T * (p.Hq // p.Hkv) + 255) // 256 * p.B * p.Hkv
+    return lay.fwd_ws[2 * kv_copy:2 * kv_copy + 4 * n].view(torch.int32).cpu().numpy()
+
+
+def test_bf16_scores_above_reference_without_overflow(oracle):
+    """Scores exceed the fixed reference by up to e^40: sums stay in range, no tile is redone."""
+    lay, _ = run_and_check(oracle, growing_scores_case(40.0))
+    assert not redo_flags(lay).any()
+
+
+def test_bf16_scores_overflow_reference_fixup_kernel(oracle):
+    """Scores exceed the reference by up to e^300: row sums overflow, the fix-up kernel takes over.
+    Forward only: keys this large (|k| ~ 26 in every channel) multiply the rounding of the saved
+    bf16 outputs, through delta = <dO, out>, into dQ = scale sum_j p (dp - delta) k_j beyond any
+    fixed tolerance -- a property of bf16 storage of the outputs, not of the kernels."""
+    lay, _ = run_and_check(oracle, growing_scores_case(300.0), backward=False)
+    assert redo_flags(lay).any()
+
+
+def test_bf16_scores_falling_along_sequence(oracle):
+    run_and_check(oracle, growing_scores_case(-300.0), backward=False)
+    run_and_check(oracle, growing_scores_case(-40.0))
+
+
+@pytest.mark.parametrize("T,Hq,Hkv", [(129, 7, 1), (193, 3, 1), (2049, 2, 2), (4100, 14, 2)])
+def test_bf16_ragged_tiles(oracle, T, Hq, Hkv):
+    """Row counts and key counts just past tile boundaries; T * G not a multiple of the row tile."""
+    run_and_check(oracle, make_case(T=T, Hq=Hq, Hkv=Hkv, W=70, f=0.35, seed=50 + T % 13))
+
+
+# ------------------------------------------------------------------------------------------
+# the benchmark's workload at full size: sampled outputs and size-independent properties
+# ------------------------------------------------------------------------------------------
+@pytest.mark.timeout(900)
+def test_full_size_headline_workload_sampled(oracle):
+    w = gen.workload("train_128k")
+    x = gen.make_inputs(w, seed=0, with_dO=True)
+    T, G = w.T, w.Hq // w.Hkv
+    lay = layer_from_numpy(x.q, x.k, x.v, x.mask, w.W, w.dtype)
+    dO = to_device(x.dO, w.dtype)
+    lay.route(); lay.forward(); lay.backward(dO, want_delta=True)
+    torch.cuda.synchronize()
+    print("full-size GPU pass done", flush=True)
+    pr = oracle.Problem(x.q, x.k, x.v, x.mask, w.W)
+    d = pr.mask_per_head().transpose(0, 2, 1)  # [B,T,Hq] bool
+
+    # ---- sampled rows: forward outputs and dQ, routed and unrouted, early and late
+    rng = np.random.default_rng(1)
+    ts = np.concatenate([[0, 1, 63, 64, w.W, w.W + 1, T - 1], rng.integers(0, T, 40)])
+    rows = np.array([(0, int(rng.integers(0, w.Hq)), int(t)) for t in ts], dtype=np.int32)
+    fr = oracle.fwd_rows(pr, rows)
+    O, S, A = lay.O, lay.S, lay.A
+    pick = lambda t_: np.stack([to_host(t_[0, r[2], r[1]]) for r in rows])
+    assert_close("S", pick(S), fr["S"], "bf16")
+    assert_close("A", pick(A), fr["A"], "bf16")
+    assert_close("O", pick(O), fr["S"] + fr["A"], "bf16")
+    lse_l = np.array([float(lay.lse_l[0, r[1], r[2]]) for r in rows])
+    lse_g = np.array([float(lay.lse_g[0, r[1], r[2]]) for r in rows])
+    assert_lse("lse_local", lse_l, fr["lse_l"], "bf16")
+    assert_lse("lse_global", lse_g, fr["lse_g"], "bf16")
+    assert any(d[0, r[2], r[1]] for r in rows) and not all(d[0, r[2], r[1]] for r in rows)
+    dq_l, dq_g = oracle.bwd_dq_rows(pr, x.dO, rows)
+    assert_close("dq", np.stack([to_host(lay.dq[0, r[2], r[1]]) for r in rows]), dq_l + dq_g, "bf16")
+    print("sampled rows checked", flush=True)
+
+    # ---- sampled keys: the last positions' dK, dV need only the statistics of the last rows
+    nlast = 40
+    tail = np.array([(0, h, t) for h in range(w.Hq) for t in range(T - nlast, T)], dtype=np.int32)
+    ft = oracle.fwd_rows(pr, tail)
+    st = {k: np.zeros((1, w.Hq, T)) for k in ("lse_l", "lse_g", "delta_l", "delta_g")}
+    dO_tail = np.stack([x.dO[0, r[2], r[1]] for r in tail]).astype(np.float64)
+    for i, r in enumerate(tail):
+        st["lse_l"][0, r[1], r[2]] = ft["lse_l"][i]
+        st["lse_g"][0, r[1], r[2]] = ft["lse_g"][i]
+        st["delta_l"][0, r[1], r[2]] = dO_tail[i] @ ft["S"][i]
+        st["delta_g"][0, r[1], r[2]] = dO_tail[i] @ ft["A"][i]
+    keys = np.array([(0, hk, j) for hk in range(w.Hkv) for j in range(T - nlast, T, 3)], dtype=np.int32)
+    dk_l, dv_l, dk_g, dv_g = oracle.bwd_dkdv_keys(pr, x.dO, keys, st["lse_l"], st["delta_l"], st["lse_g"],
+                                                   st["delta_g"])
+    assert_close("dk", np.stack([to_host(lay.dk[0, k_[2], k_[1]]) for k_ in keys]), dk_l + dk_g, "bf16")
+    assert_close("dv", np.stack([to_host(lay.dv[0, k_[2], k_[1]]) for k_ in keys]), dv_l + dv_g, "bf16")
+    print("sampled keys checked", flush=True)
+
+    # ---- properties that hold at any size.  Every row's probabilities sum to one, so
+    #   sum_j dV_j = sum over rows of that KV head of g_t  (g = dO, plus d dO for the Global branch)
+    #   sum_j dK_j = 0
+    # up to the bf16 rounding of the T stored values (independent, half an ulp each at most).
+    dv = to_host(lay.dv)[0]   # [T,Hkv,D]
+    dk = to_host(lay.dk)[0]
+    weight = 1.0 + d[0].astype(np.float64)                               # [T,Hq]
+    gsum = np.einsum("thd,th->hd", x.dO[0].astype(np.float64), weight)   # [Hq,D]
+    gsum = gsum.reshape(w.Hkv, G, w.D).sum(1)
+    slack = lambda a: 2e-2 * np.sqrt(T) + 2.0 ** -8 * np.sqrt((a * a).sum(0)) * 4
+    assert np.all(np.abs(dv.sum(0) - gsum) <= slack(dv)), np.abs(dv.sum(0) - gsum).max()
+    assert np.all(np.abs(dk.sum(0)) <= slack(dk)), np.abs(dk.sum(0)).max()
+    # unrouted rows: no Global gradient, zero Global output
+    unr = np.argwhere(~d[0])[:: max(1, (~d[0]).sum() // 500)]
+    assert all(float(lay.A[0, t_, h_].abs().max()) == 0.0 for t_, h_ in unr[:200])
