@@ -172,8 +172,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         const size_t row0 = rows_bh + (size_t)t * kRT;
         const size_t base = (size_t)s * a.set_stride + row0 * (kD * 2);
         const unsigned dst = lds_rm0 + buf * (unsigned)sizeof(RowTileLds);
-        rm_dma_issue<kRT>(rm_off, a.rows.qc + base, dst, wave);
-        rm_dma_issue<kRT>(rm_off, a.rows.gc + base, dst + kRT * 256, wave);
+        rm_dma_issue(rm_off, a.rows.qc + base, dst, wave);
+        rm_dma_issue(rm_off, a.rows.gc + base, dst + kRT * 256, wave);
         // per-row statistics: 32 rows, the upper half-wave repeats the lower one (every wavefront
         // issues them, identically, so that all wavefronts have the same number of loads in flight)
         dma4_so(a.rows.ndelta + (size_t)s * a.set_stride + row0 * 4, stat_off, dst + 2 * kRT * 256);
@@ -185,8 +185,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         const size_t base = set + (rows_bh * kD + (size_t)t * kRT) * 2;
         const size_t so = set + (rows_bh + (size_t)t * kRT) * 4;
         const unsigned dst = lds_tm0 + buf * (unsigned)sizeof(ColTileLds);
-        tm_dma_issue<kRT>(tm_off, a.rows.qt + base, dst, wave);
-        tm_dma_issue<kRT>(tm_off, a.rows.gt + base, dst + kD * kRT * 2, wave);
+        tm_dma_issue(tm_off, a.rows.qt + base, dst, wave);
+        tm_dma_issue(tm_off, a.rows.gt + base, dst + kD * kRT * 2, wave);
         dma4_so(a.rows.lse2 + so, stat_off, dst + 2 * kD * kRT * 2);
         dma4_so(a.rows.pos + so, stat_off, dst + 2 * kD * kRT * 2 + 256);
     };

@@ -110,15 +110,15 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
         const size_t src = (size_t)jb * kBK * kv_row_bytes;
         const unsigned dk_ = lds_k0 + buf * (kBK * 256), dv_ = lds_v0 + buf * (kBK * 256);
         if ((jb + 1) * kBK <= gm.T) {
-            rm_dma_issue<kBK>(kv_off, kbase + src, dk_, wave);
-            rm_dma_issue<kBK>(kv_off, vbase + src, dv_, wave);
+            rm_dma_issue(kv_off, kbase + src, dk_, wave);
+            rm_dma_issue(kv_off, vbase + src, dv_, wave);
         } else {  // keys past the end of the sequence are clamped: always masked, never out of bounds
             rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, kbase + src, dk_, wave);
             rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, vbase + src, dv_, wave);
         }
     };
     auto load_kt = [&](int jb, int buf) __attribute__((always_inline)) {
-        tm_dma_issue<kBK>(kt_off, ktbase + (size_t)jb * kBK * 2, lds_kt0 + buf * (kD * kBK * 2), wave);
+        tm_dma_issue(kt_off, ktbase + (size_t)jb * kBK * 2, lds_kt0 + buf * (kD * kBK * 2), wave);
     };
 
     f32x16 acc[4];

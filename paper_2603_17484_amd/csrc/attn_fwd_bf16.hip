@@ -111,12 +111,12 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     auto load_k = [&](int jb, int buf) __attribute__((always_inline)) {
         const char* src = kbase + (size_t)jb * kBK * kv_row_bytes;
         const unsigned dst = lds_k0 + buf * (kBK * 256);
-        if ((jb + 1) * kBK <= gm.T) rm_dma_issue<kBK>(k_off, src, dst, wave);
+        if ((jb + 1) * kBK <= gm.T) rm_dma_issue(k_off, src, dst, wave);
         else  // keys past the end of the sequence are clamped: always masked, never out of bounds
             rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, src, dst, wave);
     };
     auto load_v = [&](int jb, int buf) __attribute__((always_inline)) {
-        tm_dma_issue<kBK>(v_off, vtbase + (size_t)jb * kBK * 2, lds_v0 + buf * (kD * kBK * 2), wave);
+        tm_dma_issue(v_off, vtbase + (size_t)jb * kBK * 2, lds_v0 + buf * (kD * kBK * 2), wave);
     };
 
     f32x16 oacc[4][kNQB];

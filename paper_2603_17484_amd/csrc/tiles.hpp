@@ -69,64 +69,67 @@ __device__ __forceinline__ void dma4_so(const void* sbase, unsigned voff, unsign
                  : "memory");
 }
 
-template <int ROWS>
+// NW = wavefronts of the workgroup; every wavefront loads 1/NW of the tile.
+template <int ROWS, int NW = 4>
 struct RmDma {
-    unsigned voff[ROWS / 16];
+    unsigned voff[ROWS / (4 * NW)];
 };
-template <int ROWS>
-__device__ __forceinline__ RmDma<ROWS> rm_dma_setup(unsigned row_stride_bytes, int wave) {
-    RmDma<ROWS> d;
+template <int ROWS, int NW = 4>
+__device__ __forceinline__ RmDma<ROWS, NW> rm_dma_setup(unsigned row_stride_bytes, int wave) {
+    RmDma<ROWS, NW> d;
     const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < ROWS / 16; ++i) {
-        const int row = (i * 4 + wave) * 4 + (lane >> 4);
+    for (int i = 0; i < ROWS / (4 * NW); ++i) {
+        const int row = (i * NW + wave) * 4 + (lane >> 4);
         d.voff[i] = (unsigned)row * row_stride_bytes + (unsigned)(((lane & 15) ^ (row & 15)) * 16);
     }
     return d;
 }
 // sbase: global address of (row 0, channel 0) of the tile, wave-uniform
-template <int ROWS>
-__device__ __forceinline__ void rm_dma_issue(const RmDma<ROWS>& d, const void* sbase, unsigned lds_base, int wave) {
+template <int ROWS, int NW>
+__device__ __forceinline__ void rm_dma_issue(const RmDma<ROWS, NW>& d, const void* sbase, unsigned lds_base,
+                                             int wave) {
 #pragma unroll
-    for (int i = 0; i < ROWS / 16; ++i) dma16_so(sbase, d.voff[i], lds_base + (i * 4 + wave) * 1024);
+    for (int i = 0; i < ROWS / (4 * NW); ++i) dma16_so(sbase, d.voff[i], lds_base + (i * NW + wave) * 1024);
 }
 
 // The same tile when only the first `rows_valid` rows exist in memory: later rows repeat the last
 // valid one (their contents never matter to the caller).  Per-lane arithmetic; for ragged ends only.
-template <int ROWS>
+template <int ROWS, int NW = 4>
 __device__ __forceinline__ void rm_dma_issue_clamped(unsigned row_stride_bytes, int rows_valid, const void* sbase,
                                                      unsigned lds_base, int wave) {
     const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < ROWS / 16; ++i) {
-        const int row = (i * 4 + wave) * 4 + (lane >> 4);
+    for (int i = 0; i < ROWS / (4 * NW); ++i) {
+        const int row = (i * NW + wave) * 4 + (lane >> 4);
         const unsigned voff =
             (unsigned)min(row, rows_valid - 1) * row_stride_bytes + (unsigned)(((lane & 15) ^ (row & 15)) * 16);
-        dma16_so(sbase, voff, lds_base + (i * 4 + wave) * 1024);
+        dma16_so(sbase, voff, lds_base + (i * NW + wave) * 1024);
     }
 }
 
-template <int TOK>
+template <int TOK, int NW = 4>
 struct TmDma {
-    unsigned voff[TOK / 16];  // 128 channels * 2 TOK bytes / 4096 bytes per workgroup instruction
+    unsigned voff[TOK / (4 * NW)];  // 128 channels * 2 TOK bytes / (1024 NW) bytes per workgroup instruction
 };
-template <int TOK>
-__device__ __forceinline__ TmDma<TOK> tm_dma_setup(unsigned ch_stride_bytes, int wave) {
+template <int TOK, int NW = 4>
+__device__ __forceinline__ TmDma<TOK, NW> tm_dma_setup(unsigned ch_stride_bytes, int wave) {
     constexpr int kChunks = TOK / 8, kRowsPerSeg = 64 / kChunks;
-    TmDma<TOK> d;
+    TmDma<TOK, NW> d;
     const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < TOK / 16; ++i) {
-        const int ch = (i * 4 + wave) * kRowsPerSeg + lane / kChunks;
+    for (int i = 0; i < TOK / (4 * NW); ++i) {
+        const int ch = (i * NW + wave) * kRowsPerSeg + lane / kChunks;
         d.voff[i] = (unsigned)ch * ch_stride_bytes + (unsigned)(((lane % kChunks) ^ tm_swizzle<TOK>(ch)) * 16);
     }
     return d;
 }
 // sbase: global address of (channel 0, first token of the tile), wave-uniform
-template <int TOK>
-__device__ __forceinline__ void tm_dma_issue(const TmDma<TOK>& d, const void* sbase, unsigned lds_base, int wave) {
+template <int TOK, int NW>
+__device__ __forceinline__ void tm_dma_issue(const TmDma<TOK, NW>& d, const void* sbase, unsigned lds_base,
+                                             int wave) {
 #pragma unroll
-    for (int i = 0; i < TOK / 16; ++i) dma16_so(sbase, d.voff[i], lds_base + (i * 4 + wave) * 1024);
+    for (int i = 0; i < TOK / (4 * NW); ++i) dma16_so(sbase, d.voff[i], lds_base + (i * NW + wave) * 1024);
 }
 
 // position of token t inside its 16-token group in a token-minor copy, and the inverse
