@@ -153,19 +153,32 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
 
     // ---- loads.  Flat tile index it -> (set, tile)
     const unsigned lds_rm0 = lds_offset(&lds_rm[0]), lds_tm0 = lds_offset(&lds_tm[0]);
-    // A Local set is walked upwards; a Global set downwards from its last tile, so that all key
-    // blocks of a head read the same tile at the same step (they only stop at different tiles).
+    // A Global set is walked downwards from its last tile, so that all key blocks of a head read the
+    // same tile at the same step (they only stop at different tiles).  A Local set is walked upwards,
+    // but every key block of an XCD's chunk starts at the first tile of the chunk's *last* key block
+    // and wraps around to its own first tiles at the end: the ranges of neighbouring key blocks are
+    // shifted copies of each other, and this rotation makes them meet on the same tile at the same step.
     const bool rev0 = a.rs[0].local == 0, rev1 = a.nsets > 1 && a.rs[1].local == 0;
+    auto rotation = [&](int s, int tb, int n) __attribute__((always_inline)) {
+        if (s >= a.nsets || !a.rs[s].local || n <= 0) return 0;
+        const int nblk = (gm.T + kKeysPerWg - 1) / kKeysPerWg;
+        const int last = min((kblk / a.chunk) * a.chunk + a.chunk - 1, nblk - 1);
+        const int r = (int)(((long long)last * kKeysPerWg * gm.G) / kRT) - tb;
+        return r < n ? r : 0;  // ranges that do not overlap share nothing
+    };
+    const int rot0 = rotation(0, tb0, n0), rot1 = rotation(1, tb1, n1);
+    auto locate = [&](int it, int& s, int& t) __attribute__((always_inline)) {
+        s = it < n0 ? 0 : 1;
+        const int j = s ? it - n0 : it, n = s ? n1 : n0, rot = s ? rot1 : rot0;
+        const int tb = s ? tb1 : tb0, te = s ? te1 : te0;
+        const int jr = j + rot >= n ? j + rot - n : j + rot;
+        t = (s ? rev1 : rev0) ? te - 1 - j : tb + jr;
+    };
     // Every load is a wave-uniform base plus a per-lane offset fixed for the whole kernel.
     const RmDma<kRT> rm_off = rm_dma_setup<kRT>(kD * 2, wave);
     const TmDma<kRT> tm_off = tm_dma_setup<kRT>((unsigned)a.cap * 2u, wave);
     const unsigned stat_off = n * 4;
     const size_t rows_bh = (size_t)bh * a.cap;
-    auto locate = [&](int it, int& s, int& t) __attribute__((always_inline)) {
-        s = it < n0 ? 0 : 1;
-        if (s) t = rev1 ? te1 - 1 - (it - n0) : tb1 + (it - n0);
-        else t = rev0 ? te0 - 1 - it : tb0 + it;
-    };
     auto load_rm = [&](int it, int buf) __attribute__((always_inline)) {
         int s, t;
         locate(it, s, t);
@@ -328,25 +341,31 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 }
             }
         };
-        for (int seg = 0; seg < 6; ++seg) {
-            const int s = seg / 3, part = seg - 3 * s;
-            if (s >= a.nsets) break;
-            const int sb = s ? tb1 : tb0, sh = s ? th1 : th0, st_ = s ? tt1 : tt0, se = s ? te1 : te0;
+        // Segments in walking order; inside one the mask flag is constant.  Tiles [tb, th) need the
+        // causal mask, [th, tt) none, [tt, te) the window / ragged-end mask.
+        int it0 = 0;
+        auto walk = [&](int s, int b, int e, bool local) __attribute__((always_inline)) {  // tiles [b, e) of set s
+            const int sth = s ? th1 : th0, stt = s ? tt1 : tt0;
             const bool rev = s ? rev1 : rev0;
-            const int off = s ? n0 : 0;
-            // tiles [tb, te) of this run; walked upwards they are flat indices off + (tile - sb),
-            // walked downwards off + (se - 1 - tile), and the runs come in the order tail, middle, head
-            const int run_id = rev ? 2 - part : part;
-            const int tb = run_id == 0 ? sb : (run_id == 1 ? sh : st_);
-            const int te = run_id == 0 ? sh : (run_id == 1 ? st_ : se);
-            if (tb >= te) continue;
+#pragma unroll
+            for (int part = 0; part < 3; ++part) {
+                const int run_id = rev ? 2 - part : part;
+                const int lo = run_id == 0 ? b : max(b, run_id == 1 ? sth : stt);
+                const int hi = run_id == 0 ? min(e, sth) : (run_id == 1 ? min(e, stt) : e);
+                if (lo >= hi) continue;
+                if (run_id == 1)
+                    run(std::false_type{}, it0, it0 + (hi - lo), local);
+                else
+                    run(std::true_type{}, it0, it0 + (hi - lo), local);
+                it0 += hi - lo;
+            }
+        };
+        for (int s = 0; s < a.nsets; ++s) {
+            const int sb = s ? tb1 : tb0, se = s ? te1 : te0, rot = s ? rot1 : rot0;
             const bool local = (s ? a.rs[1].local : a.rs[0].local) != 0;
-            const int it_begin = rev ? off + (se - te) : off + (tb - sb);
-            const int it_end = it_begin + (te - tb);
-            if (run_id == 1)
-                run(std::false_type{}, it_begin, it_end, local);
-            else
-                run(std::true_type{}, it_begin, it_end, local);
+            if (sb >= se) continue;
+            walk(s, sb + rot, se, local);     // a reversed set has no rotation: the whole range
+            if (rot) walk(s, sb, sb + rot, local);
         }
     }
 
