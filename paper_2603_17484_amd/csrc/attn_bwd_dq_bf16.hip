@@ -86,7 +86,13 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
         greg[ks] = *reinterpret_cast<const bf16x8*>(a.dO + row_off + 8 * h + ks * 16);
     }
     const float neg_lse2 = -a.lse[so] * kLog2e;
+    // The dP accumulators start from -delta (delta = <dO, saved out>), so dS = P o dP' needs no
+    // subtraction, and since every row's P sums to one, sum_j dS_j = (sum_j P dP) - delta: the
+    // exact delta is the saved one plus the row sum of dS.
     const float dlt = a.delta[so];
+    f32x16 ndl16;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) ndl16[e] = -dlt;
     float dlt_exact = 0.f;
 
     // ---- block range and its three runs (window-start masks / no masks / causal diagonal)
@@ -154,7 +160,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
             if constexpr (mm < 16) {
                 constexpr int ks = mm >> 1;
                 if constexpr ((mm & 1) == 0) nxt.s = mfma32(opnd[mm], qreg[ks], ks == 0 ? zero16 : nxt.s);
-                else nxt.dp = mfma32(opnd[mm], greg[ks], ks == 0 ? zero16 : nxt.dp);
+                else nxt.dp = mfma32(opnd[mm], greg[ks], ks == 0 ? ndl16 : nxt.dp);
             } else {
                 constexpr int x = mm - 16, grp = x >> 2, d = x & 3;
                 const u32x4 dv = {dsw[grp][0], dsw[grp][1], dsw[grp][2], dsw[grp][3]};
@@ -177,8 +183,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
                 p1 = ok1 ? p1 : 0.f;
             }
             const float dp0 = cur.dp[e], dp1 = cur.dp[e + 1];
-            dsum = fmaf(p0, dp0, fmaf(p1, dp1, dsum));
-            f32x2 f = {p0 * (dp0 - dlt), p1 * (dp1 - dlt)};
+            f32x2 f = {p0 * dp0, p1 * dp1};  // dp already holds dP - delta
+            dsum += f[0] + f[1];
             dsw[grp][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
         };
 
@@ -208,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             Xa.s = mfma32(rm_operand(&lds_k[0][0], n, ks, h), qreg[ks], ks == 0 ? zero16 : Xa.s);
-            Xa.dp = mfma32(rm_operand(&lds_v[0][0], n, ks, h), greg[ks], ks == 0 ? zero16 : Xa.dp);
+            Xa.dp = mfma32(rm_operand(&lds_v[0][0], n, ks, h), greg[ks], ks == 0 ? ndl16 : Xa.dp);
         }
     }
 
@@ -238,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
 
     // ---- epilogue
     if (!wave_active) return;
-    const float de = dlt_exact + __shfl_xor(dlt_exact, 32);
+    const float de = dlt + dlt_exact + __shfl_xor(dlt_exact, 32);
     if (!valid) return;
 #pragma unroll
     for (int d = 0; d < 4; ++d)
