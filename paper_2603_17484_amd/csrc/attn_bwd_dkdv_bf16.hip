@@ -265,8 +265,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         auto ds_pair = [&](auto qc) {  // pair q in 0..7, in the order the dV / dK products consume them
             constexpr int q = decltype(qc)::value;
             constexpr int step = q >> 2, i2 = (q & 3) * 2, e = step * 8 + i2, rg = e >> 2, el = e & 3;
-            float p0 = fast_exp2(fmaf(cur.s[e], c2, -l2[rg][el]));
-            float p1 = fast_exp2(fmaf(cur.s[e + 1], c2, -l2[rg][el + 1]));
+            float p0 = fast_exp2(fmaf(acc_read(cur.s[e]), c2, -l2[rg][el]));
+            float p1 = fast_exp2(fmaf(acc_read(cur.s[e + 1]), c2, -l2[rg][el + 1]));
             if (MASK) {
                 const int rp0 = ps[rg][el], rp1 = ps[rg][el + 1];
                 bool ok0 = rp0 >= key && key < gm.T, ok1 = rp1 >= key && key < gm.T;
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 p1 = ok1 ? p1 : 0.f;
             }
             f32x2 fp = {p0, p1};
-            f32x2 fd = {p0 * cur.dp[e], p1 * cur.dp[e + 1]};  // dp already holds dP - delta
+            f32x2 fd = {p0 * acc_read(cur.dp[e]), p1 * acc_read(cur.dp[e + 1])};  // dp already holds dP - delta
             pw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fp, bf16x2));
             dsw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fd, bf16x2));
         };
@@ -295,6 +295,9 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             });
             L2A_FENCE();
         });
+        // Both S/dP buffers stay in AGPRs, where the matrix instructions write them; the VALU side
+        // fetches each element with acc_read where it is consumed.
+        asm volatile("" : "+a"(nxt.s), "+a"(nxt.dp));
     };
 
     if (total > 0) {
@@ -330,15 +333,24 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 dma_wait();
             __syncthreads();
         };
+        // The two S/dP buffers swap roles every tile; which one holds the current tile is carried
+        // across runs in `flip` (no register copies): a leading single step restores the phase,
+        // then steps come in pairs.
+        bool flip = false;  // false: Xa holds the current tile
         auto run = [&](auto mask_tag, int it_begin, int it_end, bool local) __attribute__((always_inline)) {
-            for (int it = it_begin; it < it_end; it += 2) {
+            int it = it_begin;
+            if (flip && it < it_end) {
+                one(mask_tag, Xb, Xa, it, local);
+                flip = false;
+                ++it;
+            }
+            for (; it + 1 < it_end; it += 2) {
                 one(mask_tag, Xa, Xb, it, local);
-                if (it + 1 < it_end) {
-                    one(mask_tag, Xb, Xa, it + 1, local);
-                } else {
-                    Xa.s = Xb.s;
-                    Xa.dp = Xb.dp;
-                }
+                one(mask_tag, Xb, Xa, it + 1, local);
+            }
+            if (it < it_end) {
+                one(mask_tag, Xa, Xb, it, local);
+                flip = true;
             }
         };
         // Segments in walking order; inside one the mask flag is constant.  Tiles [tb, th) need the

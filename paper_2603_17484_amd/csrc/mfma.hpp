@@ -130,4 +130,13 @@ __device__ __forceinline__ int row_code(const RowSet& rs, const Geom& gm, int bh
     return rs.row_idx ? rs.row_idx[(size_t)bh * gm.T * gm.G + r] : r;
 }
 
+// Value of an accumulator element that lives in an AGPR (the VALU cannot read AGPRs).  Written
+// out so that the copy is issued where the value is consumed, between matrix instructions,
+// instead of in a burst of copies where the compiler splits the accumulator's live range.
+__device__ __forceinline__ float acc_read(float x) {
+    float y;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(y) : "a"(x));
+    return y;
+}
+
 }  // namespace l2a
