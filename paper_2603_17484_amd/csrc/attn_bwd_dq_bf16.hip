@@ -93,6 +93,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     f32x16 ndl16;
 #pragma unroll
     for (int e = 0; e < 16; ++e) ndl16[e] = -dlt;
+    asm volatile("" : "+a"(ndl16));  // an accumulator operand: lives in AGPRs
     float dlt_exact = 0.f;
 
     // ---- block range and its three runs (window-start masks / no masks / causal diagonal)
@@ -170,8 +171,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
         auto ds_pair = [&](auto qc) {  // pair q in 0..7, in the order the dQ product consumes them
             constexpr int q = decltype(qc)::value;
             constexpr int grp = q >> 2, i2 = (q & 3) * 2, e = grp * 8 + i2;
-            float p0 = fast_exp2(fmaf(cur.s[e], c2, neg_lse2));
-            float p1 = fast_exp2(fmaf(cur.s[e + 1], c2, neg_lse2));
+            float p0 = fast_exp2(fmaf(acc_read(cur.s[e]), c2, neg_lse2));
+            float p1 = fast_exp2(fmaf(acc_read(cur.s[e + 1]), c2, neg_lse2));
             if (MASK) {
                 const int key0 = k0 + c_row(e, h), key1 = k0 + c_row(e + 1, h);
                 bool ok0 = key0 <= pos, ok1 = key1 <= pos;
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
                 p0 = ok0 ? p0 : 0.f;
                 p1 = ok1 ? p1 : 0.f;
             }
-            const float dp0 = cur.dp[e], dp1 = cur.dp[e + 1];
+            const float dp0 = acc_read(cur.dp[e]), dp1 = acc_read(cur.dp[e + 1]);
             f32x2 f = {p0 * dp0, p1 * dp1};  // dp already holds dP - delta
             dsum += f[0] + f[1];
             dsw[grp][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
@@ -201,6 +202,9 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
             L2A_FENCE();
         });
         dlt_exact += dsum;
+        // Both S/dP buffers stay in AGPRs, where the matrix instructions write them; the VALU side
+        // fetches each element with acc_read where it is consumed.
+        asm volatile("" : "+a"(nxt.s), "+a"(nxt.dp));
     };
 
     // ---- prologue: K, V of the first two blocks, token-minor K of the first; S, dP of the first half-block
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     load_kt(jb0, 0);
     dma_wait();
     __syncthreads();
-    if (wave_active) {
+    {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             Xa.s = mfma32(rm_operand(&lds_k[0][0], n, ks, h), qreg[ks], ks == 0 ? zero16 : Xa.s);
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
             const int buf = rel % 3, buf1 = (rel + 1) % 3, buf2 = (rel + 2) % 3;
             if (jb + 2 <= jb1) load_kv(jb + 2, buf2);          // that buffer held block jb-1
             if (jb + 1 <= jb1) load_kt(jb + 1, (rel + 1) & 1);  // held block jb-1
-            if (wave_active) {
+            {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
                 const __bf16* ktt = &lds_kt[rel & 1][0];
                 half_block(mask_tag, Int<0>{}, Xa, Xb, &lds_k[buf][0], &lds_v[buf][0], 32, ktt, jb * kBK);
                 half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], &lds_v[buf1][0], 0, ktt, jb * kBK + 32);

@@ -173,8 +173,8 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
         auto exp_pair = [&](auto qc) {
             constexpr int q = decltype(qc)::value;
             constexpr int grp = q >> 3, c = (q >> 2) & 1, i2 = (q & 3) * 2, r = grp * 8 + i2;
-            float p0 = fast_exp2(fmaf(cur.s[c][r], c2, negm[c]));
-            float p1 = fast_exp2(fmaf(cur.s[c][r + 1], c2, negm[c]));
+            float p0 = fast_exp2(fmaf(acc_read(cur.s[c][r]), c2, negm[c]));
+            float p1 = fast_exp2(fmaf(acc_read(cur.s[c][r + 1]), c2, negm[c]));
             if (MASK) {
                 p0 = key_ok(k0 + c_row(r, h), c) ? p0 : 0.f;
                 p1 = key_ok(k0 + c_row(r + 1, h), c) ? p1 : 0.f;
@@ -198,6 +198,9 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
         });
 #pragma unroll
         for (int c = 0; c < kNQB; ++c) l[c] += rsum[c];
+        // Both score buffers stay in AGPRs, where the matrix instructions write them; the VALU side
+        // fetches each element with acc_read where it is consumed.
+        asm volatile("" : "+a"(nxt.s[0]), "+a"(nxt.s[1]));
     };
 
     // ---- prologue: K of the first two blocks, V of the first
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     // two blocks (every row of the tile has a key there).  It is never updated: scores that come
     // later may exceed it, which costs no accuracy in floating point; the epilogue checks that the
     // row sums stayed far from overflow and otherwise leaves the tile to the fix-up kernel.
-    if (wave_active) {
+    {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
 #pragma unroll
         for (int c = 0; c < kNQB; ++c) mref[c] = -INFINITY;
         const int nb = jb0 < jb1 ? 2 : 1;
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
             // prefetch: K of block jb+2 (its buffer held block jb-1), V of block jb+1 (held block jb-1)
             if (jb + 2 <= jb1) load_k(jb + 2, kbuf2);
             if (jb + 1 <= jb1) load_v(jb + 1, (rel + 1) & 1);
-            if (wave_active) {
+            {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
                 const __bf16* vt = &lds_v[rel & 1][0];
                 half_block(mask_tag, Int<0>{}, Sa, Sb, &lds_k[kbuf][0], 32, vt, jb * kBK);
                 half_block(mask_tag, Int<1>{}, Sb, Sa, &lds_k[kbuf1][0], 0, vt, jb * kBK + 32);
