@@ -93,7 +93,6 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     f32x16 ndl16;
 #pragma unroll
     for (int e = 0; e < 16; ++e) ndl16[e] = -dlt;
-    asm volatile("" : "+a"(ndl16));  // an accumulator operand: lives in AGPRs
     float dlt_exact = 0.f;
 
     // ---- block range and its three runs (window-start masks / no masks / causal diagonal)
@@ -160,8 +159,13 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
             constexpr int mm = decltype(mc)::value;
             if constexpr (mm < 16) {
                 constexpr int ks = mm >> 1;
-                if constexpr ((mm & 1) == 0) nxt.s = mfma32(opnd[mm], qreg[ks], ks == 0 ? zero16 : nxt.s);
-                else nxt.dp = mfma32(opnd[mm], greg[ks], ks == 0 ? ndl16 : nxt.dp);
+                if constexpr (ks == 0) {
+                    if constexpr ((mm & 1) == 0) mfma32_vgpr_first(nxt.s, opnd[mm], qreg[ks]);
+                    else mfma32_vgpr_from(nxt.dp, opnd[mm], greg[ks], ndl16);
+                } else {
+                    if constexpr ((mm & 1) == 0) mfma32_vgpr_acc(nxt.s, opnd[mm], qreg[ks]);
+                    else mfma32_vgpr_acc(nxt.dp, opnd[mm], greg[ks]);
+                }
             } else {
                 constexpr int x = mm - 16, grp = x >> 2, d = x & 3;
                 const u32x4 dv = {dsw[grp][0], dsw[grp][1], dsw[grp][2], dsw[grp][3]};
@@ -171,8 +175,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
         auto ds_pair = [&](auto qc) {  // pair q in 0..7, in the order the dQ product consumes them
             constexpr int q = decltype(qc)::value;
             constexpr int grp = q >> 2, i2 = (q & 3) * 2, e = grp * 8 + i2;
-            float p0 = fast_exp2(fmaf(acc_read(cur.s[e]), c2, neg_lse2));
-            float p1 = fast_exp2(fmaf(acc_read(cur.s[e + 1]), c2, neg_lse2));
+            float p0 = fast_exp2(fmaf(cur.s[e], c2, neg_lse2));
+            float p1 = fast_exp2(fmaf(cur.s[e + 1], c2, neg_lse2));
             if (MASK) {
                 const int key0 = k0 + c_row(e, h), key1 = k0 + c_row(e + 1, h);
                 bool ok0 = key0 <= pos, ok1 = key1 <= pos;
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
                 p0 = ok0 ? p0 : 0.f;
                 p1 = ok1 ? p1 : 0.f;
             }
-            const float dp0 = acc_read(cur.dp[e]), dp1 = acc_read(cur.dp[e + 1]);
+            const float dp0 = cur.dp[e], dp1 = cur.dp[e + 1];
             f32x2 f = {p0 * dp0, p1 * dp1};  // dp already holds dP - delta
             dsum += f[0] + f[1];
             dsw[grp][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
@@ -202,9 +206,6 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
             L2A_FENCE();
         });
         dlt_exact += dsum;
-        // Both S/dP buffers stay in AGPRs, where the matrix instructions write them; the VALU side
-        // fetches each element with acc_read where it is consumed.
-        asm volatile("" : "+a"(nxt.s), "+a"(nxt.dp));
     };
 
     // ---- prologue: K, V of the first two blocks, token-minor K of the first; S, dP of the first half-block
@@ -217,9 +218,16 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            Xa.s = mfma32(rm_operand(&lds_k[0][0], n, ks, h), qreg[ks], ks == 0 ? zero16 : Xa.s);
-            Xa.dp = mfma32(rm_operand(&lds_v[0][0], n, ks, h), greg[ks], ks == 0 ? ndl16 : Xa.dp);
+            const bf16x8 ka = rm_operand(&lds_k[0][0], n, ks, h), va = rm_operand(&lds_v[0][0], n, ks, h);
+            if (ks == 0) {
+                mfma32_vgpr_first(Xa.s, ka, qreg[ks]);
+                mfma32_vgpr_from(Xa.dp, va, greg[ks], ndl16);
+            } else {
+                mfma32_vgpr_acc(Xa.s, ka, qreg[ks]);
+                mfma32_vgpr_acc(Xa.dp, va, greg[ks]);
+            }
         }
+        mfma_vgpr_settle();  // the first half-block reads Xa at once
     }
 
     auto run = [&](auto mask_tag, int j_begin, int j_end) __attribute__((always_inline)) {

@@ -139,4 +139,30 @@ __device__ __forceinline__ float acc_read(float x) {
     return y;
 }
 
+// Matrix instructions whose result tile is consumed by the VALU (scores, dP): written as inline
+// assembly with the C/D tile in VGPRs.  The compiler puts every builtin MFMA's C/D tile in AGPRs
+// when a kernel uses more than 256 registers, and then needs one v_accvgpr_read per element the
+// VALU touches -- in these kernels the VALU is the busier unit.
+// Rules the callers keep, since the compiler does not see an MFMA here and inserts no hazard
+// no-ops for it: (1) A and B come from LDS loads or from registers written long before (never
+// straight from a VALU result); (2) a tile is read by the VALU only after at least eight further
+// matrix instructions have been issued behind the last write to it; (3) a chain accumulates into
+// exactly the same registers (the hardware interlocks that case).
+// After the last write of a chain that the VALU reads right away (a kernel prologue): wait out
+// the matrix pipeline.
+__device__ __forceinline__ void mfma_vgpr_settle() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+__device__ __forceinline__ void mfma32_vgpr_first(f32x16& d, bf16x8 a, bf16x8 b) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_vgpr_from(f32x16& d, bf16x8 a, bf16x8 b, const f32x16& c) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d) : "v"(a), "v"(b), "v"(c));
+}
+__device__ __forceinline__ void mfma32_vgpr_acc(f32x16& d, bf16x8 a, bf16x8 b) {
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+}
+
 }  // namespace l2a
