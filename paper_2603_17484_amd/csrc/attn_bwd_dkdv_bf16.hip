@@ -249,8 +249,13 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             constexpr int mm = decltype(mc)::value;
             if constexpr (mm < 16) {
                 constexpr int ks = mm >> 1;
-                if constexpr ((mm & 1) == 0) nxt.s = mfma32(opnd[mm], kreg[ks], ks == 0 ? zero16 : nxt.s);
-                else nxt.dp = mfma32(opnd[mm], vreg[ks], ks == 0 ? nd : nxt.dp);
+                if constexpr (ks == 0) {
+                    if constexpr ((mm & 1) == 0) mfma32_vgpr_first(nxt.s, opnd[mm], kreg[ks]);
+                    else mfma32_vgpr_from(nxt.dp, opnd[mm], vreg[ks], nd);
+                } else {
+                    if constexpr ((mm & 1) == 0) mfma32_vgpr_acc(nxt.s, opnd[mm], kreg[ks]);
+                    else mfma32_vgpr_acc(nxt.dp, opnd[mm], vreg[ks]);
+                }
             } else {
                 constexpr int x = mm - 16, step = x >> 3, d = (x >> 1) & 3;
                 if constexpr ((x & 1) == 0) {
@@ -265,8 +270,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         auto ds_pair = [&](auto qc) {  // pair q in 0..7, in the order the dV / dK products consume them
             constexpr int q = decltype(qc)::value;
             constexpr int step = q >> 2, i2 = (q & 3) * 2, e = step * 8 + i2, rg = e >> 2, el = e & 3;
-            float p0 = fast_exp2(fmaf(acc_read(cur.s[e]), c2, -l2[rg][el]));
-            float p1 = fast_exp2(fmaf(acc_read(cur.s[e + 1]), c2, -l2[rg][el + 1]));
+            float p0 = fast_exp2(fmaf(cur.s[e], c2, -l2[rg][el]));
+            float p1 = fast_exp2(fmaf(cur.s[e + 1], c2, -l2[rg][el + 1]));
             if (MASK) {
                 const int rp0 = ps[rg][el], rp1 = ps[rg][el + 1];
                 bool ok0 = rp0 >= key && key < gm.T, ok1 = rp1 >= key && key < gm.T;
@@ -278,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 p1 = ok1 ? p1 : 0.f;
             }
             f32x2 fp = {p0, p1};
-            f32x2 fd = {p0 * acc_read(cur.dp[e]), p1 * acc_read(cur.dp[e + 1])};  // dp already holds dP - delta
+            f32x2 fd = {p0 * cur.dp[e], p1 * cur.dp[e + 1]};  // dp already holds dP - delta
             pw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fp, bf16x2));
             dsw[step][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(fd, bf16x2));
         };
@@ -295,9 +300,6 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             });
             L2A_FENCE();
         });
-        // Both S/dP buffers stay in AGPRs, where the matrix instructions write them; the VALU side
-        // fetches each element with acc_read where it is consumed.
-        asm volatile("" : "+a"(nxt.s), "+a"(nxt.dp));
     };
 
     if (total > 0) {
@@ -315,9 +317,12 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         for (int e = 0; e < 16; ++e) Xa.dp[e] = lds_rm[0].ndelta[c_row(e, h)];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            Xa.s = mfma32(rm_operand(lds_rm[0].q_rm, n, ks, h), kreg[ks], ks == 0 ? zero16 : Xa.s);
-            Xa.dp = mfma32(rm_operand(lds_rm[0].g_rm, n, ks, h), vreg[ks], Xa.dp);
+            const bf16x8 qa = rm_operand(lds_rm[0].q_rm, n, ks, h), ga = rm_operand(lds_rm[0].g_rm, n, ks, h);
+            if (ks == 0) mfma32_vgpr_first(Xa.s, qa, kreg[ks]);
+            else mfma32_vgpr_acc(Xa.s, qa, kreg[ks]);
+            mfma32_vgpr_acc(Xa.dp, ga, vreg[ks]);
         }
+        mfma_vgpr_settle();  // the first tile step reads Xa at once
 
         // Step `it` reads the row-major tile it+1 and the token-minor tile it, and starts the loads
         // of row-major tile it+kNB (into the buffer tile `it` left one step ago) and token-minor tile
