@@ -145,8 +145,12 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
  *                          equals its *_loc partner the two gradients are summed into that one
  *                          buffer (shared projections); all three must then alias.
  *                          Rows of dq_glb for tokens with d = 0 are zero.
- *   delta_glb_opt     out optional [B,Hq,T] float: <dO_t, a_t>, the task-loss part of the
- *                          router-score gradient (Sec. 3.3 Eq. 7); zero where d = 0
+ *   delta_glb_opt     out optional [B,Hq,T] float: <dO_t, A_t>, the task-loss part of the
+ *                          router-score gradient (Sec. 3.3 Eq. 7), for every token: zero where A is.
+ *                          For the training steps that compute Global attention for all tokens
+ *                          (Sec. 3.3), pass as A and lse_global the outputs of a Global-only
+ *                          L2A_FLAG_DENSE forward together with the sparse row lists: the q/k/v
+ *                          gradients still come from the routed rows only, delta_glb covers all.
  */
 int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const void* k_loc,
                  const void* v_loc, const void* q_glb, const void* k_glb, const void* v_glb,

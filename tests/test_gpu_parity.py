@@ -274,8 +274,10 @@ def test_bf16_ragged_tiles(oracle, T, Hq, Hkv):
 # the benchmark's workload at full size: sampled outputs and size-independent properties
 # ------------------------------------------------------------------------------------------
 @pytest.mark.timeout(900)
-def test_full_size_headline_workload_sampled(oracle):
-    w = gen.workload("train_128k")
+@pytest.mark.parametrize("name", ["train_128k", "qwen3_8b_128k"])
+def test_full_size_workload_sampled(oracle, name):
+    """The benchmark's workload (train_128k) and the Hq=32 / Hkv=8 bursty per-head one, at T = 131072."""
+    w = gen.workload(name)
     x = gen.make_inputs(w, seed=0, with_dO=True)
     T, G = w.T, w.Hq // w.Hkv
     lay = layer_from_numpy(x.q, x.k, x.v, x.mask, w.W, w.dtype)
@@ -338,3 +340,72 @@ def test_full_size_headline_workload_sampled(oracle):
     # unrouted rows: no Global gradient, zero Global output
     unr = np.argwhere(~d[0])[:: max(1, (~d[0]).sum() // 500)]
     assert all(float(lay.A[0, t_, h_].abs().max()) == 0.0 for t_, h_ in unr[:200])
+
+
+@pytest.mark.timeout(600)
+def test_full_size_prefill_bursty_shared_mask_sampled(oracle):
+    """Forward only, T = 131072, one bursty mask shared by all heads (every routed position is G rows)."""
+    w = gen.workload("prefill_128k")
+    x = gen.make_inputs(w, seed=0, with_dO=False)
+    lay = layer_from_numpy(x.q, x.k, x.v, x.mask, w.W, w.dtype)
+    lay.route(); lay.forward()
+    torch.cuda.synchronize()
+    pr = oracle.Problem(x.q, x.k, x.v, x.mask, w.W)
+    d = pr.mask_per_head().transpose(0, 2, 1)
+    rng = np.random.default_rng(2)
+    on = np.flatnonzero(x.mask[0, 0])
+    starts = on[np.flatnonzero(np.diff(on, prepend=-2) > 1)]          # first token of some bursts
+    ts = np.concatenate([[0, w.T - 1], rng.choice(starts, 12), rng.choice(starts, 6) - 1, rng.integers(0, w.T, 20)])
+    ts = np.clip(ts, 0, w.T - 1)
+    rows = np.array([(0, int(rng.integers(0, w.Hq)), int(t)) for t in ts], dtype=np.int32)
+    fr = oracle.fwd_rows(pr, rows)
+    pick = lambda t_: np.stack([to_host(t_[0, r[2], r[1]]) for r in rows])
+    assert_close("S", pick(lay.S), fr["S"], "bf16")
+    assert_close("A", pick(lay.A), fr["A"], "bf16")
+    assert_close("O", pick(lay.O), fr["S"] + fr["A"], "bf16")
+    assert_lse("lse_global", np.array([float(lay.lse_g[0, r[1], r[2]]) for r in rows]), fr["lse_g"], "bf16")
+    assert any(d[0, r[2], r[1]] for r in rows) and not all(d[0, r[2], r[1]] for r in rows)
+
+
+# ------------------------------------------------------------------------------------------
+# real head layout, whole tensors
+# ------------------------------------------------------------------------------------------
+@pytest.mark.timeout(900)
+def test_bf16_qwen_head_layout_whole_tensors(oracle):
+    """Hq = 28, Hkv = 4, D = 128 at a length the oracle still finishes: every element of every output."""
+    run_and_check(oracle, make_case(T=3000, Hq=28, Hkv=4, W=700, Hm=28, f=0.2, seed=60))
+
+
+# ------------------------------------------------------------------------------------------
+# training variant with Global attention for every token (Sec. 3.3), composed from the same calls
+# ------------------------------------------------------------------------------------------
+def test_global_for_all_training_variant(oracle):
+    """With a small probability a training step computes Global attention for all tokens, still
+    merges o = s + d a with the router's decisions, and back-propagates <dO_t, a_t> to the router for
+    every token (Sec. 3.3, Eq. 7).  Composition: a dense Global-only forward gives a_t and its
+    log-sum-exp for all t; the normal sparse forward gives O and S; the backward call takes the
+    dense A and log-sum-exp with the sparse row lists, so q/k/v gradients still come from routed
+    rows only while delta_glb is <dO_t, a_t> for every t."""
+    x = make_case(T=700, Hq=6, Hkv=2, W=90, Hm=6, f=0.3, seed=70)
+    w = x.w
+    pr = oracle.Problem(x.q, x.k, x.v, x.mask, w.W)
+    pr_all = oracle.Problem(x.q, x.k, x.v, np.ones_like(x.mask), w.W)
+    ref, ref_all = oracle.layer_fwd(pr), oracle.layer_fwd(pr_all)
+    g = oracle.layer_bwd(pr, x.dO, ref)
+
+    sparse = layer_from_numpy(x.q, x.k, x.v, x.mask, w.W, w.dtype)
+    dense = layer_from_numpy(x.q, x.k, x.v, x.mask, w.W, w.dtype, flags=B.L2A_FLAG_DENSE | B.L2A_FLAG_SKIP_LOCAL)
+    sparse.route(); sparse.forward()
+    dense.forward()
+    torch.cuda.synchronize()
+    assert_close("O", to_host(sparse.O), ref["S"] + ref["A"], w.dtype)          # forward unchanged
+    assert_close("A", to_host(dense.A), ref_all["A"], w.dtype)                  # a_t for every token
+    sparse.A, sparse.lse_g = dense.A, dense.lse_g                               # hand the dense branch to the backward
+    sparse.backward(to_device(x.dO, w.dtype), want_delta=True)
+    torch.cuda.synchronize()
+    assert_close("dq", to_host(sparse.dq), g["dq_l"] + g["dq_g"], w.dtype)
+    assert_close("dk", to_host(sparse.dk), g["dk_l"] + g["dk_g"], w.dtype)
+    assert_close("dv", to_host(sparse.dv), g["dv_l"] + g["dv_g"], w.dtype)
+    delta_all = np.einsum("bthd,bthd->bht", x.dO.astype(np.float64), ref_all["A"])
+    err = np.abs(to_host(sparse.delta_g) - delta_all).max()
+    assert err <= 3e-2, f"router-gradient factor <dO, a> max err {err}"
