@@ -56,6 +56,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="train_128k")
     ap.add_argument("--fraction", type=float, default=None, help="override the routed fraction")
+    ap.add_argument("--seq-len", type=int, default=None, help="override the workload's sequence length T")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-dense", action="store_true", help="skip timing the dense all-routed mode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -82,8 +83,13 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = gen.workload(args.workload)
+    over = {}
     if args.fraction is not None:
-        w = gen.workload(args.workload, routed_fraction=args.fraction)
+        over["routed_fraction"] = args.fraction
+    if args.seq_len is not None:
+        over["T"] = args.seq_len
+    if over:
+        w = gen.workload(args.workload, **over)
     backward = w.backward and not args.forward_only
     D, T = w.D, w.T
 
@@ -165,7 +171,7 @@ def main() -> int:
     }
     dom = max((n for n in kern if n in alg), key=lambda n: kern[n])
     achieved = alg[dom] / (kern[dom] * 1e-3) / 1e12
-    default_workload = (args.workload == "train_128k" and args.fraction is None and args.seed == 0 and backward)
+    default_workload = (args.workload == "train_128k" and not over and args.seed == 0 and backward)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if default_workload else None,
@@ -179,7 +185,7 @@ def main() -> int:
 
     out = {
         "metric": "L2A layer effective TFLOP/s (route_compact + fwd + bwd, T=131072, 80% of tokens skip Global)"
-                  if args.workload == "train_128k" and args.fraction is None else
+                  if args.workload == "train_128k" and not over else
                   f"L2A layer effective TFLOP/s ({w.name})",
         "value": round(tflops_layer, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_sparse, 3), "higher_is_better": True, "scaling": "weak",
