@@ -150,6 +150,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
         bf16x8 opnd[16 + kAhead];
         uint32_t pw[kNQB][2][4];  // P as packed bf16 pairs: [row block][16-key group][dword]
         float rsum[kNQB];
+        const bf16x2 one2 = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int c = 0; c < kNQB; ++c) rsum[c] = 0.f;
         // operand o: o < 8 -> K rows of the next half-block (ks = o); else V^T (16-key group, channel block)
@@ -179,9 +180,12 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
                 p0 = key_ok(k0 + c_row(r, h), c) ? p0 : 0.f;
                 p1 = key_ok(k0 + c_row(r + 1, h), c) ? p1 : 0.f;
             }
-            rsum[c] += p0 + p1;
             f32x2 f = {p0, p1};
-            pw[c][grp][i2 >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+            const bf16x2 pb = __builtin_convertvector(f, bf16x2);
+            pw[c][grp][i2 >> 1] = __builtin_bit_cast(uint32_t, pb);
+            // row sum of the weights as the matrix cores will see them (rounded to bf16): one
+            // v_dot2 per pair, and the normalisation is exact for the weights actually used
+            rsum[c] = __builtin_amdgcn_fdot2_f32_bf16(pb, one2, rsum[c], false);
         };
 
         static_for<0, kAhead>([&](auto oc) { read_operand(oc); });
