@@ -12,6 +12,8 @@
  *                            and the w tokens before it                                (Sec. 2)
  *   Conditional global       a_t = GlobalAttn(...) if d_t = 1, else 0                  (Sec. 3.1, Eq. 4)
  *   Merge                    o_t = s_t + a_t * d_t                                     (Sec. 3.1, Eq. 5)
+ *   Router                   dhat_t = sigmoid(<w, x_t> + bias), d_t = [dhat_t >= tau]   (Sec. 3.1, Eq. 3;
+ *                            tau = 0.5 in training, a knob at test time)
  *   Compaction               ascending list of the active queries' positions (Q_idx)   (Sec. 3.2; App. C, Alg. 1 step 1)
  *   Backward                 the paper only says gradients are taken for active queries
  *                            with the saved log-sum-exp (Sec. 3.2); the formulas are the
@@ -84,6 +86,27 @@ static void attend(const oracle_dims* p, const float* qv, const float* k, const 
         for (int i = 0; i < D; ++i) out[i] += pj * (double)vj[i];
     }
     *lse = m + log(l);
+}
+
+/* ---------------------------------------------------------------------------------------
+ * Router (Sec. 3.1 Eq. 3): score and decision of every token from its router input x_t [C].
+ *   logit[b,t] = <w, x[b,t,:]> + bias;  dhat = 1 / (1 + exp(-logit));  d = 1 iff dhat >= tau,
+ * taken on the logit: logit >= ln(tau / (1 - tau)), which is the same comparison without the
+ * rounding of the sigmoid.  x is fp32 storage; everything else fp64.
+ * ------------------------------------------------------------------------------------- */
+void l2a_oracle_router(int32_t B, int32_t T, int32_t C, const float* x, const double* w, double bias, double tau,
+                       double* logit, double* dhat, uint8_t* d) {
+    const double thr = log(tau / (1.0 - tau));
+#pragma omp parallel for schedule(static)
+    for (long long i = 0; i < (long long)B * T; ++i) {
+        const float* xi = x + (size_t)i * C;
+        double acc = 0.0;
+        for (int c = 0; c < C; ++c) acc += w[c] * (double)xi[c];
+        acc += bias;
+        logit[i] = acc;
+        dhat[i] = 1.0 / (1.0 + exp(-acc));
+        d[i] = acc >= thr ? 1 : 0;
+    }
 }
 
 /* ---------------------------------------------------------------------------------------

@@ -131,6 +131,21 @@ def route_compact(mask: np.ndarray, Hq: int, Hkv: int):
 
 
 # ------------------------------------------------------------------------------------
+# router  (Sec. 3.1 Eq. 3)
+# ------------------------------------------------------------------------------------
+def router(x: np.ndarray, w: np.ndarray, bias: float = 0.0, tau: float = 0.5):
+    """x [B,T,C], w [C] -> logit, dhat [B,T] float64 and d [B,1,T] uint8 (a mask shared by all heads)."""
+    x = _f32(x)
+    B, T, C = x.shape
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    assert w.shape == (C,) and 0.0 < tau < 1.0
+    logit = np.empty((B, T)); dhat = np.empty((B, T)); d = np.empty((B, T), dtype=np.uint8)
+    _load().l2a_oracle_router(ctypes.c_int32(B), ctypes.c_int32(T), ctypes.c_int32(C), _p(x), _p(w),
+                              ctypes.c_double(bias), ctypes.c_double(tau), _p(logit), _p(dhat), _p(d))
+    return logit, dhat, d.reshape(B, 1, T)
+
+
+# ------------------------------------------------------------------------------------
 # forward
 # ------------------------------------------------------------------------------------
 def fwd_rows(pr: Problem, rows: np.ndarray):

@@ -266,3 +266,41 @@ def test_masks_have_requested_statistics():
     b = gen.make_inputs(gen.workload("tiny_fp32", T=64), seed=3)
     np.testing.assert_array_equal(a.q, b.q)
     assert a.mask[0, 0, 0] == 1 and a.dO is not None
+
+
+# ------------------------------------------------------------------------------------------
+# router (Sec. 3.1 Eq. 3)
+# ------------------------------------------------------------------------------------------
+def test_router_zero_weights_route_every_token(oracle):
+    """A zero-initialised router scores 0.5 everywhere, so with tau = 0.5 every token takes Global
+    attention (the initial state of a converted model, Sec. 3.1)."""
+    x = np.random.default_rng(0).standard_normal((2, 37, 24)).astype(np.float32)
+    logit, dhat, d = oracle.router(x, np.zeros(24))
+    assert np.all(logit == 0.0) and np.all(dhat == 0.5) and d.all() and d.shape == (2, 1, 37)
+
+
+def test_router_against_scipy_and_threshold_monotone(oracle):
+    from scipy.special import expit, logit as sp_logit
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((1, 500, 64)).astype(np.float32)
+    w = rng.standard_normal(64) * 0.3
+    lg, dhat, d = oracle.router(x, w, bias=0.25, tau=0.5)
+    ref = x.astype(np.float64) @ w + 0.25
+    assert np.allclose(lg, ref, rtol=0, atol=1e-12)
+    assert np.allclose(dhat, expit(ref), rtol=0, atol=1e-15)
+    assert np.array_equal(d[:, 0], (ref >= 0).astype(np.uint8))
+    prev = None
+    for tau in (0.1, 0.3, 0.5, 0.7, 0.9):       # a higher threshold routes a subset
+        _, _, dt = oracle.router(x, w, bias=0.25, tau=tau)
+        assert np.array_equal(dt[:, 0], (ref >= sp_logit(tau)).astype(np.uint8))
+        if prev is not None:
+            assert np.all(dt <= prev)
+        prev = dt
+
+
+def test_router_one_hot_weight_reads_one_channel(oracle):
+    x = np.random.default_rng(2).standard_normal((3, 50, 16)).astype(np.float32)
+    w = np.zeros(16); w[5] = 2.0
+    lg, _, d = oracle.router(x, w)
+    assert np.array_equal(lg, 2.0 * x[:, :, 5].astype(np.float64))
+    assert np.array_equal(d[:, 0], (x[:, :, 5] >= 0).astype(np.uint8))
