@@ -147,6 +147,29 @@ def main() -> int:
     flops_routed = mult * D * pg
     tflops_layer = flops_layer / (ms_sparse * 1e-3) / 1e12
 
+    # ---- router front-end on the Local branch's output viewed as [B, T, Hq*D]: an HBM-bound pass
+    router = None
+    if True:
+        C = w.Hq * D
+        xr = (sparse.S if backward else sparse.O).view(w.B, T, C)
+        wr = torch.randn(C, generator=g, device=dev, dtype=torch.float32) / C ** 0.5
+        rmask = torch.empty((w.B, 1, T), dtype=torch.uint8, device=dev)
+        rdhat = torch.empty((w.B, T), dtype=torch.float32, device=dev)
+        for _ in range(2):
+            B.l2a_router_decide(sparse.p, xr, wr, 0.0, 0.5, rmask, rdhat)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            B.l2a_router_decide(sparse.p, xr, wr, 0.0, 0.5, rmask, rdhat)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_r = e0.elapsed_time(e1) / 10
+        nbytes = w.B * T * C * 2 + w.B * T * 5 + C * 4          # x once, mask + score out, w
+        router = {"ms": round(ms_r, 4), "bytes": nbytes, "achieved_GBps": round(nbytes / ms_r / 1e6, 1),
+                  "peak_GBps": 8000.0, "frac": round(nbytes / ms_r / 1e6 / 8000.0, 4), "bound": "hbm",
+                  "input": f"[{w.B},{T},{C}] bf16"}
+        del rmask, rdhat, wr
+
     # ---- global branch alone (routed FLOPs only)
     ms_glob = tflops_routed = None
     if not args.sparse_only:
@@ -204,6 +227,7 @@ def main() -> int:
             "kernels_ms": {n: round(t, 3) for n, t in kern_dense.items()}},
         "kernels_ms": {n: round(t, 3) for n, t in kern.items()},
         "roofline": roofline,
+        "router_front_end": router,
         "cpu_baseline": cpu,
         "paper_context": "paper reports ~10x fwd / ~8x bwd kernel speed-ups over FlashAttention-2 at 128K and up "
                          "to 90% sparsity on NVIDIA H200 (Fig. 1 caption, Sec. 4.2); not comparable hardware",

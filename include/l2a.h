@@ -109,6 +109,27 @@ int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx
                       int32_t* kblk_first_row, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Router front-end (Sec. 3.1 Eq. 3; the threshold is 0.5 in training and a knob at test time):
+ *     logit_t = <w, x_t> + bias,   dhat_t = sigmoid(logit_t),   d_t = 1 iff dhat_t >= tau,
+ * the decision being taken on the logit (logit_t >= ln(tau / (1 - tau))).  The mask it writes is
+ * the input of l2a_route_compact with mask_heads = 1.  Only B, T and dtype of `p` are used (the
+ * other fields must still be valid).  fp32 accumulation; HBM-bound, x is read once.
+ *
+ *   C          channels of the router input, a multiple of 8
+ *   x          in  [B,T,C] router input of every token, element type p->dtype (the Local module's
+ *                  output; for a router that reads the raw local attention output, S viewed as
+ *                  [B,T,Hq*D])
+ *   w          in  [C] float
+ *   logit_opt  out optional [B,T] float
+ *   dhat_opt   out optional [B,T] float: the score, for the sparsity regulariser and the
+ *                  straight-through gradient (Sec. 3.3 Eqs. 6, 7)
+ *   mask       out [B,1,T] uint8, 0 or 1
+ * Errors: L2A_ERR_SHAPE for C not a positive multiple of 8 or tau outside (0,1).
+ */
+int l2a_router_decide(const l2a_params* p, int32_t C, const void* x, const float* w, float bias, float tau,
+                      float* logit_opt, float* dhat_opt, uint8_t* mask, void* stream);
+
+/*
  * Forward (Sec. 3.1 Eqs. 2, 4, 5; App. C Alg. 1).
  *
  *   q_loc,k_loc,v_loc  in  inputs of the Local branch

@@ -21,8 +21,8 @@ L2A_FLAG_DENSE, L2A_FLAG_SKIP_LOCAL, L2A_FLAG_SKIP_GLOBAL = 1, 2, 4
 L2A_FLAG_SCALAR = 1 << 16
 
 EXPORTS = ("l2a_version", "l2a_strerror", "l2a_route_workspace_bytes", "l2a_attn_workspace_bytes",
-           "l2a_kblk_entries", "l2a_route_compact", "l2a_attn_fwd", "l2a_attn_bwd", "l2a_profile_enable",
-           "l2a_profile_read")
+           "l2a_kblk_entries", "l2a_route_compact", "l2a_router_decide", "l2a_attn_fwd", "l2a_attn_bwd",
+           "l2a_profile_enable", "l2a_profile_read")
 
 
 class l2a_params(ctypes.Structure):
@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.l2a_kblk_entries.argtypes = [ctypes.c_int32]
         L.l2a_route_compact.restype = ctypes.c_int
         L.l2a_route_compact.argtypes = [pp, vp, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+        L.l2a_router_decide.restype = ctypes.c_int
+        L.l2a_router_decide.argtypes = [pp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
         L.l2a_attn_fwd.restype = ctypes.c_int
         L.l2a_attn_fwd.argtypes = [pp] + [vp] * 6 + [i32p] * 3 + [vp] * 5 + [vp, ctypes.c_size_t, vp]
         L.l2a_attn_bwd.restype = ctypes.c_int
@@ -105,6 +107,14 @@ def l2a_route_compact(p: l2a_params, mask: torch.Tensor, row_idx: torch.Tensor, 
                                  _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream())
     if rc != 0:
         raise L2AError(rc, "l2a_route_compact")
+
+
+def l2a_router_decide(p: l2a_params, x: torch.Tensor, w: torch.Tensor, bias: float, tau: float, mask: torch.Tensor,
+                      dhat: Optional[torch.Tensor] = None, logit: Optional[torch.Tensor] = None) -> None:
+    rc = lib().l2a_router_decide(ctypes.byref(p), int(x.shape[-1]), _ptr(x), _ptr(w), float(bias), float(tau),
+                                 _ptr(logit), _ptr(dhat), _ptr(mask), _stream())
+    if rc != 0:
+        raise L2AError(rc, "l2a_router_decide")
 
 
 def l2a_attn_fwd(p: l2a_params, q_loc, k_loc, v_loc, q_glb, k_glb, v_glb, row_idx, count, kblk_first_row, O,

@@ -69,6 +69,10 @@ int simple_bwd_dkdv(const Geom& g, int dtype, const RowSet* sets, int nsets, con
                     const void* v, const void* dO, const float* const* lse, const float* const* delta, void* dk,
                     void* dv, hipStream_t st);
 
+// ---- router.hip : logit = <w, x_t> + bias; mask = [logit >= thr]; optional sigmoid score and logit
+int router_decide(const l2a_params& p, int C, const void* x, const float* w, float bias, float thr, float* logit,
+                  float* dhat, uint8_t* mask, hipStream_t st);
+
 // ---- util.hip
 int row_deltas(const Geom& g, int dtype, const void* dO, const void* S, const void* A, float* delta_l,
                float* delta_g, hipStream_t st);

@@ -2,6 +2,8 @@
 // Every step of the layer runs in the kernels of this library; nothing here computes.
 #include "common.hpp"
 
+#include <cmath>
+
 using namespace l2a;
 
 namespace {
@@ -105,6 +107,17 @@ int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx
     if (!workspace || workspace_bytes < route_workspace_bytes(*p)) return L2A_ERR_WORKSPACE;
     if (misaligned(row_idx) || misaligned(workspace)) return L2A_ERR_ALIGN;
     return route_compact(*p, mask, row_idx, count, kblk_first_row, workspace, (hipStream_t)stream);
+}
+
+int l2a_router_decide(const l2a_params* p, int32_t C, const void* x, const float* w, float bias, float tau,
+                      float* logit_opt, float* dhat_opt, uint8_t* mask, void* stream) {
+    const int rc = check_params(p);
+    if (rc != L2A_OK) return rc;
+    if (C < 8 || C % 8 != 0 || !(tau > 0.f && tau < 1.f)) return L2A_ERR_SHAPE;
+    if (!x || !w || !mask) return L2A_ERR_NULL;
+    if (misaligned(x) || misaligned(w)) return L2A_ERR_ALIGN;
+    const float thr = (float)std::log((double)tau / (1.0 - (double)tau));
+    return router_decide(*p, C, x, w, bias, thr, logit_opt, dhat_opt, mask, (hipStream_t)stream);
 }
 
 int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, const void* v_loc,

@@ -106,3 +106,15 @@ def test_null_alignment_and_workspace_errors(lib):
     # dense mode needs no index arrays and no compaction work
     p.flags = B.L2A_FLAG_DENSE
     assert lib.l2a_route_compact(ctypes.byref(p), None, None, None, None, None, 0, None) == 0
+
+
+def test_router_argument_errors(lib):
+    p = B.make_params(1, 128, 4, 2, 128, 16)
+    x = ctypes.c_void_p(0x1000)
+    call = lambda C, xp, wp, tau, mp: lib.l2a_router_decide(ctypes.byref(p), C, xp, wp, ctypes.c_float(0.0),
+                                                           ctypes.c_float(tau), None, None, mp, None)
+    assert call(12, x, x, 0.5, x) == -2          # C not a multiple of 8
+    assert call(0, x, x, 0.5, x) == -2
+    assert call(64, x, x, 0.0, x) == -2 and call(64, x, x, 1.0, x) == -2   # tau outside (0, 1)
+    assert call(64, None, x, 0.5, x) == -1 and call(64, x, None, 0.5, x) == -1 and call(64, x, x, 0.5, None) == -1
+    assert call(64, ctypes.c_void_p(0x1004), x, 0.5, x) == -5

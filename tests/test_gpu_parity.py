@@ -409,3 +409,44 @@ def test_global_for_all_training_variant(oracle):
     delta_all = np.einsum("bthd,bthd->bht", x.dO.astype(np.float64), ref_all["A"])
     err = np.abs(to_host(sparse.delta_g) - delta_all).max()
     assert err <= 3e-2, f"router-gradient factor <dO, a> max err {err}"
+
+
+# ------------------------------------------------------------------------------------------
+# router front-end (Sec. 3.1 Eq. 3)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,C,T", [("bf16", 3584, 1000), ("fp32", 512, 333), ("bf16", 8, 5), ("bf16", 1032, 4097)])
+@pytest.mark.parametrize("tau", [0.5, 0.2])
+def test_router_decide(oracle, dtype, C, T, tau):
+    """Scores against the fp64 oracle; decisions must agree wherever the fp64 logit is not within the
+    fp32 accumulation error of the threshold (there either answer is a correct fp32 decision)."""
+    rng = np.random.default_rng(C + T)
+    Bn = 2
+    x = rng.standard_normal((Bn, T, C)).astype(np.float32)
+    if dtype == "bf16":
+        x = gen.round_to_bf16(x)
+    w = (rng.standard_normal(C) / np.sqrt(C)).astype(np.float32)
+    bias = 0.1
+    lg, dhat, d = oracle.router(x, w.astype(np.float64), bias, tau)
+    p = B.make_params(Bn, T, 4, 2, 128, 16, 1, B.L2A_BF16 if dtype == "bf16" else B.L2A_FP32)
+    xd = to_device(x, dtype)
+    wd = torch.from_numpy(w).cuda()
+    mask = torch.full((Bn, 1, T), 7, dtype=torch.uint8, device="cuda")
+    dh = torch.empty((Bn, T), dtype=torch.float32, device="cuda")
+    lo = torch.empty((Bn, T), dtype=torch.float32, device="cuda")
+    B.l2a_router_decide(p, xd, wd, bias, tau, mask, dh, lo)
+    torch.cuda.synchronize()
+    got_lg, got_dh, got_d = lo.cpu().numpy().astype(np.float64), dh.cpu().numpy().astype(np.float64), mask.cpu().numpy()
+    # fp32 sum of C products of O(1/sqrt(C)) terms: a few 1e-7 per unit of |logit| ~ 1
+    assert np.abs(got_lg - lg).max() <= 2e-5
+    assert np.abs(got_dh - dhat).max() <= 1e-5
+    thr = np.log(tau / (1 - tau))
+    sure = np.abs(lg - thr) > 2e-5
+    assert sure.mean() > 0.99
+    assert np.array_equal(got_d[:, 0][sure], d[:, 0][sure])
+    assert set(np.unique(got_d)) <= {0, 1}
+    # the mask feeds the compaction as a shared one
+    row_idx, count, first, ws = B.alloc_route(p)
+    B.l2a_route_compact(p, mask, row_idx, count, first, ws)
+    torch.cuda.synchronize()
+    r, c, k = oracle.route_compact(got_d, 4, 2)
+    assert np.array_equal(row_idx.cpu().numpy(), r) and np.array_equal(count.cpu().numpy(), c)
