@@ -61,9 +61,11 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true", help="skip timing the dense all-routed mode")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-step measurement")
     ap.add_argument("--sparse-only", action="store_true",
-                    help="run nothing but the timed workload (no routed-only pass, dense mode or CPU oracle), so that "
-                         "every launch a profiler sees belongs to it")
+                    help="no routed-only pass, dense mode or CPU oracle: every launch of the layer's kernels that a "
+                         "profiler sees then belongs to the timed workload (the router and decode kernels, measured "
+                         "separately, have names of their own)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of 1 GiB (a known-size kernel to scale profiler byte counters)")
     args = ap.parse_args()
@@ -170,6 +172,11 @@ def main() -> int:
                   "input": f"[{w.B},{T},{C}] bf16"}
         del rmask, rdhat, wr
 
+    # ---- decode step (Sec. 3.4) on a batch of sequences with full-length caches: an HBM-bound pass
+    decode = None
+    if not args.no_decode:
+        decode = decode_leg(torch, B, w, dev, g)
+
     # ---- global branch alone (routed FLOPs only)
     ms_glob = tflops_routed = None
     if not args.sparse_only:
@@ -228,12 +235,44 @@ def main() -> int:
         "kernels_ms": {n: round(t, 3) for n, t in kern.items()},
         "roofline": roofline,
         "router_front_end": router,
+        "decode_step": decode,
         "cpu_baseline": cpu,
         "paper_context": "paper reports ~10x fwd / ~8x bwd kernel speed-ups over FlashAttention-2 at 128K and up "
                          "to 90% sparsity on NVIDIA H200 (Fig. 1 caption, Sec. 4.2); not comparable hardware",
     }
     print(json.dumps(out))
     return 0
+
+
+def decode_leg(torch, B, w, dev, g, batch=8):
+    """One decode step for `batch` sequences whose caches hold T tokens each: every sequence routed, and
+    one in four routed.  Algorithmic bytes: each K and V row in reach once per branch that runs."""
+    T, D = w.T, w.D
+    mk = lambda *s: torch.randn(*s, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    kc, vc, qn = mk(batch, T, w.Hkv, D), mk(batch, T, w.Hkv, D), mk(batch, w.Hq, D)
+    pos = torch.full((batch,), T - 1, dtype=torch.int32, device=dev)
+    p = B.make_params(batch, T, w.Hq, w.Hkv, D, w.W, 1)
+    O = torch.empty((batch, w.Hq, D), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(B.lib().l2a_decode_workspace_bytes(__import__("ctypes").byref(p)), dtype=torch.uint8, device=dev)
+    out = {"batch": batch, "cache_tokens": T, "peak_GBps": 8000.0, "bound": "hbm"}
+    row_bytes = w.Hkv * D * 2 * 2   # K and V
+    for name, routed in (("all_routed", batch), ("one_in_four_routed", batch // 4)):
+        d = torch.zeros((batch, 1), dtype=torch.uint8, device=dev)
+        d[:routed] = 1
+        run = lambda: B.l2a_attn_decode(p, qn, kc, vc, pos, d, O, workspace=ws)
+        for _ in range(3):
+            run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        nbytes = (batch * (w.W + 1) + routed * T) * row_bytes
+        out[name] = {"ms": round(ms, 4), "bytes": nbytes, "achieved_GBps": round(nbytes / ms / 1e6, 1),
+                     "frac": round(nbytes / ms / 1e6 / 8000.0, 4)}
+    return out
 
 
 def cpu_baseline(w, q, k, v, dO, mask_np, backward, seed, budget_s=15.0):

@@ -151,6 +151,30 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
                  void* stream);
 
 /*
+ * Decode step (Sec. 3.4): one new token per sequence against the KV cache.  Local attention over
+ * the last W+1 keys for every token; Global attention over keys 0..pos only for heads whose
+ * decision is 1 -- skipped entirely, cache not read, when no head of a KV group is routed; merged
+ * as o = s + d a (Sec. 3.1 Eq. 5).  bf16, D = 128, Hq / Hkv <= 16; both branches read the same
+ * q / cache (for separate Local and Global modules call twice with L2A_FLAG_SKIP_GLOBAL /
+ * L2A_FLAG_SKIP_LOCAL).  HBM-bound: every cache row in reach is read once per branch.
+ *
+ *   p->T        capacity of the cache in tokens (the row stride of k_cache / v_cache)
+ *   q           in  [B,Hq,D]      the new token's queries
+ *   k_cache,v_cache  in  [B,T,Hkv,D]  rows 0..pos[b] valid (the new token's own K, V included)
+ *   pos         in  [B] int32, device memory: position of the new token, 0 <= pos[b] < T
+ *   mask        in  [B,mask_heads] uint8, device memory: the new token's decisions
+ *                   (NULL allowed with L2A_FLAG_DENSE)
+ *   O           out [B,Hq,D]
+ *   lse_local, lse_global  out optional [B,Hq]; lse_global is -inf where d = 0
+ *   S_opt, A_opt  out optional [B,Hq,D]; A is zero where d = 0
+ *   workspace   l2a_decode_workspace_bytes(p): one partial (max, sum, O) per 512 keys, head and branch
+ */
+size_t l2a_decode_workspace_bytes(const l2a_params* p);
+int l2a_attn_decode(const l2a_params* p, const void* q, const void* k_cache, const void* v_cache,
+                    const int32_t* pos, const uint8_t* mask, void* O, float* lse_local, float* lse_global,
+                    void* S_opt, void* A_opt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Backward (Sec. 3.2: gradients only for the active queries, reusing the saved log-sum-exp
  * and Q_idx; the formulas are the standard softmax-attention gradient).  With g_t = dO_t for
  * the Local branch and d_t dO_t for the Global branch (from Eq. 5):

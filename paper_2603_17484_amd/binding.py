@@ -22,6 +22,7 @@ L2A_FLAG_SCALAR = 1 << 16
 
 EXPORTS = ("l2a_version", "l2a_strerror", "l2a_route_workspace_bytes", "l2a_attn_workspace_bytes",
            "l2a_kblk_entries", "l2a_route_compact", "l2a_router_decide", "l2a_attn_fwd", "l2a_attn_bwd",
+           "l2a_decode_workspace_bytes", "l2a_attn_decode",
            "l2a_profile_enable", "l2a_profile_read")
 
 
@@ -62,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.l2a_route_compact.argtypes = [pp, vp, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.l2a_router_decide.restype = ctypes.c_int
         L.l2a_router_decide.argtypes = [pp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
+        L.l2a_decode_workspace_bytes.restype = ctypes.c_size_t
+        L.l2a_decode_workspace_bytes.argtypes = [pp]
+        L.l2a_attn_decode.restype = ctypes.c_int
+        L.l2a_attn_decode.argtypes = [pp] + [vp] * 10 + [vp, ctypes.c_size_t, vp]
         L.l2a_attn_fwd.restype = ctypes.c_int
         L.l2a_attn_fwd.argtypes = [pp] + [vp] * 6 + [i32p] * 3 + [vp] * 5 + [vp, ctypes.c_size_t, vp]
         L.l2a_attn_bwd.restype = ctypes.c_int
@@ -115,6 +120,17 @@ def l2a_router_decide(p: l2a_params, x: torch.Tensor, w: torch.Tensor, bias: flo
                                  _ptr(logit), _ptr(dhat), _ptr(mask), _stream())
     if rc != 0:
         raise L2AError(rc, "l2a_router_decide")
+
+
+def l2a_attn_decode(p: l2a_params, q, k_cache, v_cache, pos, mask, O, lse_local=None, lse_global=None, S_opt=None,
+                    A_opt=None, workspace=None) -> None:
+    if workspace is None:
+        workspace = _ws(lib().l2a_decode_workspace_bytes(ctypes.byref(p)), q.device)
+    rc = lib().l2a_attn_decode(ctypes.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(pos), _ptr(mask), _ptr(O),
+                               _ptr(lse_local), _ptr(lse_global), _ptr(S_opt), _ptr(A_opt), _ptr(workspace),
+                               workspace.numel() if workspace is not None else 0, _stream())
+    if rc != 0:
+        raise L2AError(rc, "l2a_attn_decode")
 
 
 def l2a_attn_fwd(p: l2a_params, q_loc, k_loc, v_loc, q_glb, k_glb, v_glb, row_idx, count, kblk_first_row, O,

@@ -12,7 +12,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libl2a.so")
 
 SOURCES = ["l2a_api.hip", "route_compact.hip", "attn_simple.hip", "util.hip", "attn_fwd_bf16.hip",
-           "attn_bwd_dq_bf16.hip", "attn_bwd_dkdv_bf16.hip", "pack.hip", "router.hip", "profile.hip"]
+           "attn_bwd_dq_bf16.hip", "attn_bwd_dkdv_bf16.hip", "pack.hip", "router.hip", "attn_decode_bf16.hip",
+           "profile.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

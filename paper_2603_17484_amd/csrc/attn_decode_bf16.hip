@@ -1,0 +1,322 @@
+// Decode step of the layer (Sec. 3.4): one new token per sequence attends to the KV cache --
+// Local attention over the last W+1 keys for every token, Global attention over the whole prefix
+// only if the token's router decision is 1, skipped entirely otherwise -- and the two are merged
+// as o = s + d a (Sec. 3.1 Eq. 5).  HBM-bound: the cache is read once per branch that runs.
+//
+// Split-key scheme, two launches:
+//   decode_partial_kernel  grid (key chunks of 512-2048, branch, batch x KV head).  The G query heads
+//       of a KV group are the rows of one 32-row matrix tile (rows >= G are padding), so K and V
+//       are read once for all of them.  Each wavefront takes 32-key sub-blocks of the chunk: K and
+//       V rows go global -> LDS with direct loads (two buffers, the next sub-block is in flight
+//       while this one is computed), S^T = K Q^T and O^T += V^T P^T run on the matrix cores with
+//       the streaming softmax of App. C Alg. 1 in between; V^T operands are transposed on the way
+//       out of LDS (ds_read_b64_tr_b16).  The four wavefronts' partial (max, sum, O) are merged in
+//       LDS and written once per chunk.
+//   decode_combine_kernel  one workgroup per (batch, query head): merges the chunks of each
+//       branch, writes S, A, the log-sum-exps and O = S + d A.
+#include "tiles.hpp"
+
+namespace l2a {
+namespace {
+
+constexpr int kMinChunk = 512;  // keys per workgroup: 512, 1024 or 2048, chosen per launch
+constexpr int kSub = 32;     // keys per wavefront step
+constexpr int kPart = kD + 4;  // floats per partial: max (log2 units), sum, 2 unused, O[128]
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+struct DecodeArgs {
+    Geom gm;            // gm.T = capacity of the cache (tokens per sequence)
+    const __bf16* q;    // [B, Hq, D]
+    const __bf16* k;    // [B, T, Hkv, D]
+    const __bf16* v;
+    const int32_t* pos; // [B] position of the new token (keys 0..pos are valid)
+    const uint8_t* mask;  // [B, mask_heads]; nullptr: every head routed
+    int mask_heads;
+    int do_local, do_global;
+    float* part;        // [B*Hq][2][nchunks][kPart]
+    int nchunks;        // chunks per sequence, = ceil(T / chunk)
+    int chunk;
+    __bf16* O;          // [B, Hq, D]
+    __bf16* S;
+    __bf16* A;
+    float* lse_l;       // [B, Hq]
+    float* lse_g;
+};
+
+__device__ __forceinline__ bool head_routed(const DecodeArgs& a, int b, int head) {
+    if (!a.mask) return true;
+    const int mh = a.mask_heads == 1 ? 0 : (a.mask_heads == a.gm.Hq ? head : head / a.gm.G);
+    return a.mask[(size_t)b * a.mask_heads + mh] != 0;
+}
+
+// A operand of O^T += V^T P^T from a row-major tile of 32 keys in the transposed-read swizzle: channel d*32+n, the
+// keys of 16-key group `step` in the order 4h..4h+3, 8+4h..8+4h+3 (the order P^T's rows come in).
+__device__ __forceinline__ bf16x8 v_transposed_operand(const __bf16* tile, int d, int step, int lane) {
+    const int i = lane & 15, n16 = (lane >> 4) & 1, h = lane >> 5;
+    const int ch = d * 32 + 16 * n16 + 4 * (i & 3);
+    const int row = 16 * step + 4 * h + (i >> 2);
+    auto addr = [&](int r) { return tile + r * 128 + (((ch >> 3) ^ rm_tr_swizzle(r)) * 8) + (ch & 7); };
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(__attribute__((address_space(3))) const void*)addr(row));
+    const s16x4 v2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(__attribute__((address_space(3))) const void*)addr(row + 8));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v1, v2, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+__global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) {
+    // per wavefront: two buffers of (K tile, V tile), 32 keys x 128 channels each
+    __shared__ __attribute__((aligned(1024))) __bf16 lds[4][2][2][kSub * 128];
+
+    const Geom& gm = a.gm;
+    const int bh = blockIdx.z, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
+    const int branch = blockIdx.y;  // 0 local, 1 global
+    const int chunk = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 31, h = lane >> 5;
+
+    const int t = a.pos[b];
+    if (branch == 0 ? !a.do_local : !a.do_global) return;
+    if (branch == 1) {  // Global attention is skipped entirely when no head of the group is routed
+        bool any = false;
+        for (int g = 0; g < gm.G; ++g) any = any || head_routed(a, b, hk * gm.G + g);
+        if (!any) return;
+    }
+    const int lo = branch == 0 ? max(t - gm.W, 0) : 0, hi = t;  // keys lo..hi
+    const int c0 = chunk * a.chunk;
+    if (c0 > hi || c0 + a.chunk <= lo) return;
+    const int kb = max(c0, lo) / kSub, ke = min(c0 + a.chunk - 1, hi) / kSub;  // sub-blocks kb..ke of this chunk
+
+    // Q of the group's heads as B operands: lane n = row (head in group), rows >= G repeat the last head
+    const int head = hk * gm.G + min(n, gm.G - 1);
+    bf16x8 qreg[8];
+    {
+        const __bf16* qp = a.q + ((size_t)b * gm.Hq + head) * kD + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    }
+
+    const unsigned kv_row_bytes = (unsigned)gm.Hkv * kD * 2;
+    const char* kbase = (const char*)(a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD);
+    const char* vbase = (const char*)(a.v + ((size_t)b * gm.T * gm.Hkv + hk) * kD);
+    const RmDma<kSub, 1> off = rm_dma_setup<kSub, 1>(kv_row_bytes, 0);
+    const RmDma<kSub, 1> off_tr = rm_tr_dma_setup<kSub, 1>(kv_row_bytes, 0);
+    const unsigned lds0 = lds_offset(&lds[0][0][0][0]) + wave * (unsigned)sizeof(lds[0]);
+    auto load = [&](int sb, int buf) __attribute__((always_inline)) {
+        const size_t src = (size_t)sb * kSub * kv_row_bytes;
+        const unsigned dst = lds0 + buf * (unsigned)sizeof(lds[0][0]);
+        if ((sb + 1) * kSub <= gm.T) {
+            rm_dma_issue(off, kbase + src, dst, 0);
+            rm_dma_issue(off_tr, vbase + src, dst + kSub * 256, 0);
+        } else {  // ragged end of the cache: rows past it repeat the last one (always masked)
+            rm_dma_issue_clamped<kSub, 1>(kv_row_bytes, gm.T - sb * kSub, kbase + src, dst, 0);
+            const int valid = gm.T - sb * kSub;
+#pragma unroll
+            for (int i = 0; i < kSub / 4; ++i) {
+                const int row = i * 4 + (lane >> 4);
+                dma16_so(vbase + src, (unsigned)min(row, valid - 1) * kv_row_bytes +
+                                          (unsigned)(((lane & 15) ^ rm_tr_swizzle(row)) * 16),
+                         dst + kSub * 256 + i * 1024);
+            }
+        }
+    };
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[d][r] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // this wavefront's sub-blocks: kb + wave, kb + wave + 4, ...
+    int sb = kb + wave;
+    if (sb <= ke) load(sb, 0);
+    for (int it = 0; sb <= ke; sb += 4, ++it) {
+        const int buf = it & 1;
+        if (sb + 4 <= ke) {
+            load(sb + 4, buf ^ 1);
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");  // the 16 loads just issued may stay in flight
+        } else {
+            dma_wait();
+        }
+        const __bf16* kt = &lds[wave][buf][0][0];
+        const __bf16* vt = &lds[wave][buf][1][0];
+
+        // S^T[key, row] = K Q^T
+        f32x16 s = zero16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) s = mfma32(rm_operand(kt, n, ks, h), qreg[ks], s);
+
+        // streaming softmax, one row per lane (the lane 32 apart holds the row's other 16 keys)
+        const int k0 = sb * kSub;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = k0 + c_row(r, h);
+            s[r] = (key >= lo && key <= hi) ? s[r] * gm.scale_log2 : -INFINITY;
+            mx = fmaxf(mx, s[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mnew = fmaxf(m, mx);  // every sub-block of the range has a valid key: mnew is finite
+        const float alpha = fast_exp2(m - mnew);  // exp2(-inf) = 0 on the first step
+        m = mnew;
+        float rsum = 0.f;
+        uint32_t pw[2][4];
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = fast_exp2(s[r] - mnew), p1 = fast_exp2(s[r + 1] - mnew);
+            rsum += p0 + p1;
+            f32x2 f = {p0, p1};
+            pw[r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+        }
+        l = l * alpha + rsum;
+        if (__any(alpha != 1.f)) {  // the running maximum of some row grew
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+        }
+
+        // O^T[ch, row] += V^T P^T
+#pragma unroll
+        for (int step = 0; step < 2; ++step) {
+            const u32x4 pv = {pw[step][0], pw[step][1], pw[step][2], pw[step][3]};
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                oacc[d] = mfma32(v_transposed_operand(vt, d, step, lane), __builtin_bit_cast(bf16x8, pv), oacc[d]);
+        }
+    }
+    l += __shfl_xor(l, 32);
+
+    // ---- merge the four wavefronts in LDS (rows < G only), one partial per chunk
+    __syncthreads();  // every wavefront is done with its tiles
+    float* stage = reinterpret_cast<float*>(&lds[0][0][0][0]);  // [4 waves][G][kPart]
+    if (n < gm.G) {
+        float* dst = stage + ((size_t)wave * gm.G + n) * kPart;
+        if (h == 0) {
+            dst[0] = m;
+            dst[1] = l;
+        }
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dst[4 + d * 32 + c_row(r, h)] = oacc[d][r];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < gm.G * kD; idx += kThreads) {
+        const int g = idx / kD, c = idx - g * kD;
+        float mm = -INFINITY;
+        for (int w = 0; w < 4; ++w) mm = fmaxf(mm, stage[((size_t)w * gm.G + g) * kPart]);
+        float ll = 0.f, oo = 0.f;
+        for (int w = 0; w < 4; ++w) {
+            const float* src = stage + ((size_t)w * gm.G + g) * kPart;
+            const float sc = src[0] == -INFINITY ? 0.f : fast_exp2(src[0] - mm);
+            ll += src[1] * sc;
+            oo += src[4 + c] * sc;
+        }
+        float* out = a.part + ((((size_t)b * gm.Hq + hk * gm.G + g) * 2 + branch) * a.nchunks + chunk) * kPart;
+        out[4 + c] = oo;
+        if (c == 0) {
+            out[0] = mm;
+            out[1] = ll;
+        }
+    }
+}
+
+// 256 threads: thread = (channel, half); the two halves take alternate chunks with a running
+// maximum (loads of successive chunks are independent, the loop is unrolled) and meet in LDS.
+__global__ __launch_bounds__(2 * kD) void decode_combine_kernel(DecodeArgs a) {
+    __shared__ float sm[2][kD], sl[2][kD], so[2][kD];
+    const Geom& gm = a.gm;
+    const int bhq = blockIdx.x, b = bhq / gm.Hq, head = bhq - b * gm.Hq;
+    const int c = threadIdx.x & (kD - 1), half = threadIdx.x >> 7;
+    const int t = a.pos[b];
+    float out[2] = {0.f, 0.f};
+    float lse[2] = {-INFINITY, -INFINITY};
+    for (int branch = 0; branch < 2; ++branch) {
+        const bool on = branch == 0 ? a.do_local != 0 : (a.do_global && head_routed(a, b, head));
+        if (!on) continue;  // uniform over the workgroup
+        const int lo = branch == 0 ? max(t - gm.W, 0) : 0;
+        const int c_lo = lo / a.chunk, c_hi = t / a.chunk;
+        const float* base = a.part + (((size_t)bhq * 2 + branch) * a.nchunks) * kPart;
+        float mm = -INFINITY, ll = 0.f, oo = 0.f;
+#pragma unroll 8
+        for (int ch = c_lo + half; ch <= c_hi; ch += 2) {
+            const float* src = base + (size_t)ch * kPart;
+            const float m1 = src[0], l1 = src[1], o1 = src[4 + c];
+            const float mn = fmaxf(mm, m1);
+            const float s0 = fast_exp2(mm - mn), s1 = fast_exp2(m1 - mn);  // exp2(-inf) = 0 on the first chunk
+            ll = ll * s0 + l1 * s1;
+            oo = oo * s0 + o1 * s1;
+            mm = mn;
+        }
+        __syncthreads();
+        sm[half][c] = mm, sl[half][c] = ll, so[half][c] = oo;
+        __syncthreads();
+        const float m0 = sm[0][c], m1 = sm[1][c];  // half 1 may have had no chunk: -inf, 0, 0
+        const float mn = fmaxf(m0, m1);
+        const float s0 = fast_exp2(m0 - mn), s1 = m1 == -INFINITY ? 0.f : fast_exp2(m1 - mn);
+        const float lsum = sl[0][c] * s0 + sl[1][c] * s1;
+        out[branch] = (so[0][c] * s0 + so[1][c] * s1) / lsum;
+        lse[branch] = (mn + __builtin_amdgcn_logf(lsum)) * kLn2;
+    }
+    if (half) return;
+    const size_t o = (size_t)bhq * kD + c;
+    a.O[o] = (__bf16)(out[0] + out[1]);
+    if (a.S) a.S[o] = (__bf16)out[0];
+    if (a.A) a.A[o] = (__bf16)out[1];
+    if (c == 0) {
+        if (a.lse_l) a.lse_l[bhq] = lse[0];
+        if (a.lse_g) a.lse_g[bhq] = lse[1];
+    }
+}
+
+}  // namespace
+
+size_t decode_partial_floats(const Geom& g) {
+    const int nchunks = (g.T + kMinChunk - 1) / kMinChunk;
+    return (size_t)g.B * g.Hq * 2 * nchunks * kPart;
+}
+
+int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, const int32_t* pos, const uint8_t* mask,
+                int mask_heads, int do_local, int do_global, float* part, void* O, void* S, void* A, float* lse_l,
+                float* lse_g, hipStream_t st) {
+    if (g.D != kD || g.G > 32) return L2A_ERR_UNSUPPORTED;
+    DecodeArgs a{};
+    a.gm = g;
+    a.q = (const __bf16*)q;
+    a.k = (const __bf16*)k;
+    a.v = (const __bf16*)v;
+    a.pos = pos;
+    a.mask = mask;
+    a.mask_heads = mask_heads;
+    a.do_local = do_local;
+    a.do_global = do_global;
+    a.part = part;
+    // long chunks amortise a workgroup's start-up latency; short ones keep every CU busy
+    a.chunk = kMinChunk;
+    for (int c = 4 * kMinChunk; c > kMinChunk; c /= 2)
+        if ((long long)g.B * g.Hkv * ((g.T + c - 1) / c) >= 1024) {
+            a.chunk = c;
+            break;
+        }
+    a.nchunks = (g.T + a.chunk - 1) / a.chunk;
+    a.O = (__bf16*)O;
+    a.S = (__bf16*)S;
+    a.A = (__bf16*)A;
+    a.lse_l = lse_l;
+    a.lse_g = lse_g;
+    {
+        KernelTimer kt("decode_partial", st);
+        hipLaunchKernelGGL(decode_partial_kernel, dim3(a.nchunks, 2, g.B * g.Hkv), dim3(kThreads), 0, st, a);
+    }
+    {
+        KernelTimer kt("decode_combine", st);
+        hipLaunchKernelGGL(decode_combine_kernel, dim3(g.B * g.Hq), dim3(2 * kD), 0, st, a);
+    }
+    return launch_status();
+}
+
+}  // namespace l2a

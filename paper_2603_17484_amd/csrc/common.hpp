@@ -86,6 +86,12 @@ int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, cons
              int vt_cap, int32_t* redo, const FwdOut& out, hipStream_t st);
 size_t mfma_fwd_redo_entries(const Geom& g);
 
+// ---- attn_decode_bf16.hip : one new token per sequence against the KV cache (bf16, D = 128)
+size_t decode_partial_floats(const Geom& g);
+int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, const int32_t* pos, const uint8_t* mask,
+                int mask_heads, int do_local, int do_global, float* part, void* O, void* S, void* A, float* lse_l,
+                float* lse_g, hipStream_t st);
+
 // ---- pack.hip : layout pre-passes (token-minor copies for the matrix-core kernels)
 int pack_kv(const Geom& g, const void* x, void* xt, int cap, hipStream_t st);
 int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, const float* lse, const float* delta,

@@ -120,6 +120,29 @@ int l2a_router_decide(const l2a_params* p, int32_t C, const void* x, const float
     return router_decide(*p, C, x, w, bias, thr, logit_opt, dhat_opt, mask, (hipStream_t)stream);
 }
 
+size_t l2a_decode_workspace_bytes(const l2a_params* p) {
+    if (check_params(p) != L2A_OK || !use_mfma(*p)) return 0;
+    return decode_partial_floats(make_geom(*p)) * sizeof(float);
+}
+
+int l2a_attn_decode(const l2a_params* p, const void* q, const void* k_cache, const void* v_cache, const int32_t* pos,
+                    const uint8_t* mask, void* O, float* lse_local, float* lse_global, void* S_opt, void* A_opt,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_params(p);
+    if (rc != L2A_OK) return rc;
+    if (!use_mfma(*p) || p->Hq / p->Hkv > 32) return L2A_ERR_UNSUPPORTED;
+    const bool dense = p->flags & L2A_FLAG_DENSE;
+    if (!q || !k_cache || !v_cache || !pos || !O || (!dense && !mask)) return L2A_ERR_NULL;
+    const void* ptrs[] = {q, k_cache, v_cache, O, S_opt, A_opt};
+    for (const void* x : ptrs)
+        if (x && misaligned(x)) return L2A_ERR_ALIGN;
+    if (!workspace || workspace_bytes < l2a_decode_workspace_bytes(p)) return L2A_ERR_WORKSPACE;
+    if (misaligned(workspace)) return L2A_ERR_ALIGN;
+    return mfma_decode(make_geom(*p), q, k_cache, v_cache, pos, dense ? nullptr : mask, p->mask_heads,
+                       !(p->flags & L2A_FLAG_SKIP_LOCAL), !(p->flags & L2A_FLAG_SKIP_GLOBAL), (float*)workspace, O,
+                       S_opt, A_opt, lse_local, lse_global, (hipStream_t)stream);
+}
+
 int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, const void* v_loc,
                  const void* q_glb, const void* k_glb, const void* v_glb, const int32_t* row_idx,
                  const int32_t* count, const int32_t* kblk_first_row, void* O, float* lse_local,

@@ -85,6 +85,21 @@ __device__ __forceinline__ RmDma<ROWS, NW> rm_dma_setup(unsigned row_stride_byte
     }
     return d;
 }
+// The same tile with the chunk permutation that suits *transposed* reads (ds_read_b64_tr_b16 of
+// 4 rows x 16 channels per 16 lanes): slot = c ^ (4 (r & 3) + ((r >> 2) & 3)), so that the four
+// rows one read touches fall into four different groups of banks.  Row reads stay conflict-free.
+__device__ __forceinline__ int rm_tr_swizzle(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+template <int ROWS, int NW = 4>
+__device__ __forceinline__ RmDma<ROWS, NW> rm_tr_dma_setup(unsigned row_stride_bytes, int wave) {
+    RmDma<ROWS, NW> d;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < ROWS / (4 * NW); ++i) {
+        const int row = (i * NW + wave) * 4 + (lane >> 4);
+        d.voff[i] = (unsigned)row * row_stride_bytes + (unsigned)(((lane & 15) ^ rm_tr_swizzle(row)) * 16);
+    }
+    return d;
+}
 // sbase: global address of (row 0, channel 0) of the tile, wave-uniform
 template <int ROWS, int NW>
 __device__ __forceinline__ void rm_dma_issue(const RmDma<ROWS, NW>& d, const void* sbase, unsigned lds_base,

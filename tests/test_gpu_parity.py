@@ -450,3 +450,101 @@ def test_router_decide(oracle, dtype, C, T, tau):
     torch.cuda.synchronize()
     r, c, k = oracle.route_compact(got_d, 4, 2)
     assert np.array_equal(row_idx.cpu().numpy(), r) and np.array_equal(count.cpu().numpy(), c)
+
+
+# ------------------------------------------------------------------------------------------
+# decode step (Sec. 3.4): one new token per sequence against the KV cache
+# ------------------------------------------------------------------------------------------
+def decode_case(oracle, Bn, Tcap, Hq, Hkv, W, pos, Hm, f, seed, flags=0):
+    """The oracle is the layer's definition at row t = pos[b]: whatever the cache holds beyond pos is
+    out of reach of a causal row, so the same K/V arrays serve as the cache."""
+    rng = np.random.default_rng(seed)
+    D = 128
+    k = gen.normal_tensor((Bn, Tcap, Hkv, D), seed, 1, "bf16")
+    v = gen.normal_tensor((Bn, Tcap, Hkv, D), seed, 2, "bf16")
+    qn = gen.normal_tensor((Bn, Hq, D), seed, 3, "bf16")
+    d = (rng.random((Bn, Hm)) < f).astype(np.uint8)
+    pos = np.asarray(pos, dtype=np.int32)
+    dense = bool(flags & B.L2A_FLAG_DENSE)
+    # oracle: a [B,T,Hq,D] query tensor that is zero except at each sequence's own position
+    qfull = np.zeros((Bn, Tcap, Hq, D), np.float32)
+    mfull = np.zeros((Bn, Hm, Tcap), np.uint8)
+    for b in range(Bn):
+        qfull[b, pos[b]] = qn[b]
+        mfull[b, :, pos[b]] = 1 if dense else d[b]
+    pr = oracle.Problem(qfull, k, v, mfull, W)
+    rows = np.array([(b, h, pos[b]) for b in range(Bn) for h in range(Hq)], dtype=np.int32)
+    ref = oracle.fwd_rows(pr, rows)
+
+    p = B.make_params(Bn, Tcap, Hq, Hkv, D, W, Hm, B.L2A_BF16, flags)
+    out = {n: torch.full((Bn, Hq, D), 7.0, dtype=torch.bfloat16, device="cuda") for n in ("O", "S", "A")}
+    lse_l = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
+    lse_g = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
+    B.l2a_attn_decode(p, to_device(qn, "bf16"), to_device(k, "bf16"), to_device(v, "bf16"),
+                      torch.from_numpy(pos).cuda(), None if dense else torch.from_numpy(d).cuda(), out["O"], lse_l, lse_g,
+                      out["S"], out["A"])
+    torch.cuda.synchronize()
+    skip_l, skip_g = bool(flags & B.L2A_FLAG_SKIP_LOCAL), bool(flags & B.L2A_FLAG_SKIP_GLOBAL)
+    rs = 0 * ref["S"] if skip_l else ref["S"]
+    ra = 0 * ref["A"] if skip_g else ref["A"]
+    shp = (Bn, Hq, D)
+    assert_close("S", to_host(out["S"]), rs.reshape(shp), "bf16")
+    assert_close("A", to_host(out["A"]), ra.reshape(shp), "bf16")
+    assert_close("O", to_host(out["O"]), (rs + ra).reshape(shp), "bf16")
+    if not skip_l:
+        assert_lse("lse_local", lse_l.cpu().numpy().astype(np.float64), ref["lse_l"].reshape(Bn, Hq), "bf16")
+    if not skip_g:
+        assert_lse("lse_global", lse_g.cpu().numpy().astype(np.float64), ref["lse_g"].reshape(Bn, Hq), "bf16")
+    return d
+
+
+@pytest.mark.parametrize("Hq,Hkv,Hm", [(28, 4, 1), (8, 2, 8), (4, 4, 4), (16, 1, 1)])
+def test_decode_matches_layer_row(oracle, Hq, Hkv, Hm):
+    hm = {1: 1}.get(Hm, Hm)
+    d = decode_case(oracle, Bn=3, Tcap=3000, Hq=Hq, Hkv=Hkv, W=700, pos=[2999, 1234, 5], Hm=hm, f=0.5, seed=80 + Hq)
+    assert d.shape == (3, hm)
+
+
+@pytest.mark.parametrize("pos", [[0], [1], [31], [32], [511], [512], [513], [1023], [1500]])
+def test_decode_positions_at_tile_edges(oracle, pos):
+    decode_case(oracle, Bn=1, Tcap=1501, Hq=14, Hkv=2, W=100, pos=pos, Hm=1, f=1.0, seed=90 + pos[0])
+
+
+@pytest.mark.parametrize("W", [0, 31, 100000])
+def test_decode_window_edges(oracle, W):
+    decode_case(oracle, Bn=2, Tcap=1100, Hq=8, Hkv=2, W=W, pos=[1099, 700], Hm=8, f=0.6, seed=95)
+
+
+def test_decode_flags_and_unrouted(oracle):
+    decode_case(oracle, Bn=2, Tcap=900, Hq=8, Hkv=2, W=64, pos=[899, 10], Hm=1, f=0.0, seed=96)    # nobody routed: O = S
+    decode_case(oracle, Bn=2, Tcap=900, Hq=8, Hkv=2, W=64, pos=[899, 10], Hm=8, f=0.5, seed=97, flags=B.L2A_FLAG_DENSE)
+    decode_case(oracle, Bn=2, Tcap=900, Hq=8, Hkv=2, W=64, pos=[899, 10], Hm=8, f=0.5, seed=98, flags=B.L2A_FLAG_SKIP_LOCAL)
+    decode_case(oracle, Bn=2, Tcap=900, Hq=8, Hkv=2, W=64, pos=[899, 10], Hm=8, f=0.5, seed=99, flags=B.L2A_FLAG_SKIP_GLOBAL)
+
+
+@pytest.mark.timeout(600)
+def test_decode_full_length_cache(oracle):
+    """Qwen2.5-7B head layout, 128K cache, a routed and an unrouted sequence."""
+    rng = np.random.default_rng(5)
+    Bn, T, Hq, Hkv, D, W = 2, 131072, 28, 4, 128, 4096
+    k = gen.normal_tensor((Bn, T, Hkv, D), 5, 1, "bf16")
+    v = gen.normal_tensor((Bn, T, Hkv, D), 5, 2, "bf16")
+    qn = gen.normal_tensor((Bn, Hq, D), 5, 3, "bf16")
+    pos = np.array([T - 1, 100000], dtype=np.int32)
+    d = np.array([[1], [0]], dtype=np.uint8)
+    qfull = np.zeros((Bn, T, Hq, D), np.float32)
+    mfull = np.zeros((Bn, 1, T), np.uint8)
+    for b in range(Bn):
+        qfull[b, pos[b]] = qn[b]
+        mfull[b, 0, pos[b]] = d[b, 0]
+    pr = oracle.Problem(qfull, k, v, mfull, W)
+    rows = np.array([(b, h, pos[b]) for b in range(Bn) for h in range(Hq)], dtype=np.int32)
+    ref = oracle.fwd_rows(pr, rows)
+    p = B.make_params(Bn, T, Hq, Hkv, D, W, 1)
+    O = torch.empty((Bn, Hq, D), dtype=torch.bfloat16, device="cuda")
+    lse_g = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
+    B.l2a_attn_decode(p, to_device(qn, "bf16"), to_device(k, "bf16"), to_device(v, "bf16"), torch.from_numpy(pos).cuda(),
+                      torch.from_numpy(d).cuda(), O, None, lse_g)
+    torch.cuda.synchronize()
+    assert_close("O", to_host(O), (ref["S"] + ref["A"]).reshape(Bn, Hq, D), "bf16")
+    assert_lse("lse_global", lse_g.cpu().numpy().astype(np.float64), ref["lse_g"].reshape(Bn, Hq), "bf16")
