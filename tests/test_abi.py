@@ -118,3 +118,18 @@ def test_router_argument_errors(lib):
     assert call(64, x, x, 0.0, x) == -2 and call(64, x, x, 1.0, x) == -2   # tau outside (0, 1)
     assert call(64, None, x, 0.5, x) == -1 and call(64, x, None, 0.5, x) == -1 and call(64, x, x, 0.5, None) == -1
     assert call(64, ctypes.c_void_p(0x1004), x, 0.5, x) == -5
+
+
+def test_decode_argument_errors_and_workspace(lib):
+    p = B.make_params(2, 5000, 28, 4, 128, 4096, 1)
+    # one (max, sum, 2 unused, O[128]) partial per 512 keys, query head and branch
+    assert lib.l2a_decode_workspace_bytes(ctypes.byref(p)) == 2 * 28 * 2 * ((5000 + 511) // 512) * 132 * 4
+    x = ctypes.c_void_p(0x1000)
+    big = ctypes.c_size_t(1 << 30)
+    call = lambda q=x, k=x, v=x, pos=x, m=x, O=x, ws=x, n=big, pp=p: lib.l2a_attn_decode(
+        ctypes.byref(pp), q, k, v, pos, m, O, None, None, None, None, ws, n, None)
+    assert call(q=None) == -1 and call(k=None) == -1 and call(pos=None) == -1 and call(m=None) == -1 and call(O=None) == -1
+    assert call(ws=None) == -4 and call(n=ctypes.c_size_t(16)) == -4
+    assert call(q=ctypes.c_void_p(0x1008)) == -5
+    pf = B.make_params(2, 5000, 28, 4, 128, 4096, 1, B.L2A_FP32)
+    assert call(pp=pf) == -3 and lib.l2a_decode_workspace_bytes(ctypes.byref(pf)) == 0
