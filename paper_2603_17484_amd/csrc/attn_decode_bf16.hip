@@ -7,8 +7,10 @@
 //   decode_partial_kernel  grid (key chunks of 512-2048, branch, batch x KV head).  The G query heads
 //       of a KV group are the rows of one 32-row matrix tile (rows >= G are padding), so K and V
 //       are read once for all of them.  Each wavefront takes 32-key sub-blocks of the chunk: K and
-//       V rows go global -> LDS with direct loads (two buffers, the next sub-block is in flight
-//       while this one is computed), S^T = K Q^T and O^T += V^T P^T run on the matrix cores with
+//       V rows go global -> LDS with direct loads (one 16 KB buffer per wavefront, so that two
+//       workgroups fit a CU and their eight wavefronts overlap each other's loads: that keeps
+//       more bytes in flight than double buffers in one workgroup), S^T = K Q^T and
+//       O^T += V^T P^T run on the matrix cores with
 //       the streaming softmax of App. C Alg. 1 in between; V^T operands are transposed on the way
 //       out of LDS (ds_read_b64_tr_b16).  The four wavefronts' partial (max, sum, O) are merged in
 //       LDS and written once per chunk.
@@ -21,6 +23,7 @@ namespace {
 
 constexpr int kMinChunk = 512;  // keys per workgroup: 512, 1024 or 2048, chosen per launch
 constexpr int kSub = 32;     // keys per wavefront step
+constexpr int kBufs = 1;     // LDS buffers per wavefront (1: two workgroups per CU overlap each other's loads)
 constexpr int kPart = kD + 4;  // floats per partial: max (log2 units), sum, 2 unused, O[128]
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -66,8 +69,8 @@ __device__ __forceinline__ bf16x8 v_transposed_operand(const __bf16* tile, int d
 }
 
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) {
-    // per wavefront: two buffers of (K tile, V tile), 32 keys x 128 channels each
-    __shared__ __attribute__((aligned(1024))) __bf16 lds[4][2][2][kSub * 128];
+    // per wavefront: kBufs buffers of (K tile, V tile), 32 keys x 128 channels each
+    __shared__ __attribute__((aligned(1024))) __bf16 lds[4][kBufs][2][kSub * 128];
 
     const Geom& gm = a.gm;
     const int bh = blockIdx.z, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
@@ -132,13 +135,14 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) 
 
     // this wavefront's sub-blocks: kb + wave, kb + wave + 4, ...
     int sb = kb + wave;
-    if (sb <= ke) load(sb, 0);
+    if (kBufs == 2 && sb <= ke) load(sb, 0);
     for (int it = 0; sb <= ke; sb += 4, ++it) {
-        const int buf = it & 1;
-        if (sb + 4 <= ke) {
+        const int buf = kBufs == 2 ? (it & 1) : 0;
+        if (kBufs == 2 && sb + 4 <= ke) {
             load(sb + 4, buf ^ 1);
             asm volatile("s_waitcnt vmcnt(16)" ::: "memory");  // the 16 loads just issued may stay in flight
         } else {
+            if (kBufs == 1) load(sb, 0);  // the previous step's LDS reads have all returned (their MFMAs were issued)
             dma_wait();
         }
         const __bf16* kt = &lds[wave][buf][0][0];
