@@ -548,3 +548,51 @@ def test_decode_full_length_cache(oracle):
     torch.cuda.synchronize()
     assert_close("O", to_host(O), (ref["S"] + ref["A"]).reshape(Bn, Hq, D), "bf16")
     assert_lse("lse_global", lse_g.cpu().numpy().astype(np.float64), ref["lse_g"].reshape(Bn, Hq), "bf16")
+
+
+# ------------------------------------------------------------------------------------------
+# HIP graph capture of the whole step
+# ------------------------------------------------------------------------------------------
+def test_step_replays_from_a_hip_graph(oracle):
+    """route_compact + forward + backward captured once and replayed: the library allocates nothing,
+    clears scratch with fill kernels, and every kernel is deterministic, so each replay must
+    reproduce the eager results bit for bit -- also after the inputs changed in place."""
+    x = make_case(T=1500, Hq=14, Hkv=2, W=300, Hm=14, f=0.3, seed=110)
+    lay = layer_from_numpy(x.q, x.k, x.v, x.mask, x.w.W, "bf16")
+    dO = to_device(x.dO, "bf16")
+
+    def step():
+        lay.route(); lay.forward(); lay.backward(dO)
+
+    step()                       # eager: allocates the gradient buffers and workspaces
+    torch.cuda.synchronize()
+    names = ("O", "S", "A", "lse_l", "lse_g", "dq", "dk", "dv")
+    eager = {n: getattr(lay, n).clone() for n in names}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                   # warm-up on the capturing stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for n in names:
+            getattr(lay, n).fill_(3.0)            # eager work between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in names:
+            assert torch.equal(getattr(lay, n), eager[n]), f"replay {rep}: {n} differs from the eager result"
+    # new inputs in the same buffers: the replay must follow them
+    x2 = make_case(T=1500, Hq=14, Hkv=2, W=300, Hm=14, f=0.5, seed=111)
+    lay.q.copy_(to_device(x2.q, "bf16")); lay.k.copy_(to_device(x2.k, "bf16")); lay.v.copy_(to_device(x2.v, "bf16"))
+    lay.mask.copy_(torch.from_numpy(x2.mask).cuda()); dO.copy_(to_device(x2.dO, "bf16"))
+    graph.replay()
+    torch.cuda.synchronize()
+    pr = oracle.Problem(x2.q, x2.k, x2.v, x2.mask, x2.w.W)
+    ref = oracle.layer_fwd(pr)
+    g = oracle.layer_bwd(pr, x2.dO, ref)
+    assert_close("O", to_host(lay.O), ref["O"], "bf16")
+    assert_close("dq", to_host(lay.dq), g["dq_l"] + g["dq_g"], "bf16")
+    assert_close("dk", to_host(lay.dk), g["dk_l"] + g["dk_g"], "bf16")
+    assert_close("dv", to_host(lay.dv), g["dv_l"] + g["dv_g"], "bf16")
