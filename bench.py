@@ -66,6 +66,9 @@ def main() -> int:
                     help="no routed-only pass, dense mode or CPU oracle: every launch of the layer's kernels that a "
                          "profiler sees then belongs to the timed workload (the router and decode kernels, measured "
                          "separately, have names of their own)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time the sparse layer's step as replays of one captured HIP graph (removes the host's launch "
+                         "gaps, which matter below ~16K tokens); the per-kernel durations still come from eager steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of 1 GiB (a known-size kernel to scale profiler byte counters)")
     args = ap.parse_args()
@@ -114,10 +117,26 @@ def main() -> int:
         if backward:
             lay.backward(dO)
 
-    def timed(lay, steps, warmup, profile=False):
+    def timed(lay, steps, warmup, profile=False, graph=False):
         for _ in range(warmup):
             step(lay)
         torch.cuda.synchronize()
+        if graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step(lay)
+            torch.cuda.current_stream().wait_stream(side)
+            cg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(cg):
+                step(lay)
+            cg.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                cg.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / steps, {}
         if profile:
             B.profile_read()
             B.profile_enable(True)
@@ -143,6 +162,10 @@ def main() -> int:
     # ---- the timed region: K steps of the sparse layer
     sparse = build(0)
     ms_sparse, kern = timed(sparse, args.steps, args.warmup, profile=True)
+    ms_eager = None
+    if args.graph:
+        ms_eager = ms_sparse
+        ms_sparse, _ = timed(sparse, args.steps, 0, graph=True)
     pl, pg, frac = pair_counts(mask_np, w.Hq, w.Hkv, T, w.W, dense=False)
     mult = 14.0 if backward else 4.0          # fwd 4 D, bwd 10 D FLOPs per (row, key) pair
     flops_layer = mult * D * (pl + pg)
@@ -224,6 +247,8 @@ def main() -> int:
                    "mask": f"{w.mask_kind}, mask_heads={w.mask_heads}", "routed_fraction_measured": round(frac, 4),
                    "passes": "fwd+bwd" if backward else "fwd", "seed": args.seed},
         "ms_layer": round(ms_sparse, 3),
+        "launch": "hip graph replay" if args.graph else "eager",
+        "ms_layer_eager": None if ms_eager is None else round(ms_eager, 3),
         "frac_of_bf16_peak_layer": round(tflops_layer / PEAK_BF16_TFLOPS, 4),
         "routed": None if ms_glob is None else {
             "tflops": round(tflops_routed, 2), "frac_of_bf16_peak": round(tflops_routed / PEAK_BF16_TFLOPS, 4),

@@ -162,6 +162,7 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
  *   q           in  [B,Hq,D]      the new token's queries
  *   k_cache,v_cache  in  [B,T,Hkv,D]  rows 0..pos[b] valid (the new token's own K, V included)
  *   pos         in  [B] int32, device memory: position of the new token, 0 <= pos[b] < T
+ *                   (device data cannot be validated on the host: values outside are clamped into the range)
  *   mask        in  [B,mask_heads] uint8, device memory: the new token's decisions
  *                   (NULL allowed with L2A_FLAG_DENSE)
  *   O           out [B,Hq,D]

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, h = lane >> 5;
 
-    const int t = a.pos[b];
+    const int t = min(max(a.pos[b], 0), gm.T - 1);  // positions outside the cache are clamped, never followed
     if (branch == 0 ? !a.do_local : !a.do_global) return;
     if (branch == 1) {  // Global attention is skipped entirely when no head of the group is routed
         bool any = false;
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(2 * kD) void decode_combine_kernel(DecodeArgs a) {
     const Geom& gm = a.gm;
     const int bhq = blockIdx.x, b = bhq / gm.Hq, head = bhq - b * gm.Hq;
     const int c = threadIdx.x & (kD - 1), half = threadIdx.x >> 7;
-    const int t = a.pos[b];
+    const int t = min(max(a.pos[b], 0), gm.T - 1);
     float out[2] = {0.f, 0.f};
     float lse[2] = {-INFINITY, -INFINITY};
     for (int branch = 0; branch < 2; ++branch) {

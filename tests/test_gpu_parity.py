@@ -455,7 +455,7 @@ def test_router_decide(oracle, dtype, C, T, tau):
 # ------------------------------------------------------------------------------------------
 # decode step (Sec. 3.4): one new token per sequence against the KV cache
 # ------------------------------------------------------------------------------------------
-def decode_case(oracle, Bn, Tcap, Hq, Hkv, W, pos, Hm, f, seed, flags=0):
+def decode_case(oracle, Bn, Tcap, Hq, Hkv, W, pos, Hm, f, seed, flags=0, pos_given=None):
     """The oracle is the layer's definition at row t = pos[b]: whatever the cache holds beyond pos is
     out of reach of a causal row, so the same K/V arrays serve as the cache."""
     rng = np.random.default_rng(seed)
@@ -481,7 +481,8 @@ def decode_case(oracle, Bn, Tcap, Hq, Hkv, W, pos, Hm, f, seed, flags=0):
     lse_l = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
     lse_g = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
     B.l2a_attn_decode(p, to_device(qn, "bf16"), to_device(k, "bf16"), to_device(v, "bf16"),
-                      torch.from_numpy(pos).cuda(), None if dense else torch.from_numpy(d).cuda(), out["O"], lse_l, lse_g,
+                      torch.from_numpy(pos if pos_given is None else np.asarray(pos_given, dtype=np.int32)).cuda(),
+                      None if dense else torch.from_numpy(d).cuda(), out["O"], lse_l, lse_g,
                       out["S"], out["A"])
     torch.cuda.synchronize()
     skip_l, skip_g = bool(flags & B.L2A_FLAG_SKIP_LOCAL), bool(flags & B.L2A_FLAG_SKIP_GLOBAL)
@@ -520,6 +521,12 @@ def test_decode_flags_and_unrouted(oracle):
     decode_case(oracle, Bn=2, Tcap=900, Hq=8, Hkv=2, W=64, pos=[899, 10], Hm=8, f=0.5, seed=97, flags=B.L2A_FLAG_DENSE)
     decode_case(oracle, Bn=2, Tcap=900, Hq=8, Hkv=2, W=64, pos=[899, 10], Hm=8, f=0.5, seed=98, flags=B.L2A_FLAG_SKIP_LOCAL)
     decode_case(oracle, Bn=2, Tcap=900, Hq=8, Hkv=2, W=64, pos=[899, 10], Hm=8, f=0.5, seed=99, flags=B.L2A_FLAG_SKIP_GLOBAL)
+
+
+def test_decode_positions_outside_the_cache_are_clamped(oracle):
+    """pos lives in device memory, so the host cannot reject it: the kernels clamp it into 0..T-1."""
+    decode_case(oracle, Bn=3, Tcap=777, Hq=8, Hkv=2, W=64, pos=[776, 0, 776], Hm=1, f=1.0, seed=100,
+                pos_given=[777, -5, 2 ** 31 - 1])
 
 
 @pytest.mark.timeout(600)
