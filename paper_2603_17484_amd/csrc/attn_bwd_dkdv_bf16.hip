@@ -129,9 +129,9 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             r_mid = kend * gm.G;
         } else {
             const int32_t* first = rs.kblk_first_row + (size_t)bh * (nkb + 1);
-            rb = first[k0 >> 6];
-            re = rs.count[bh];
-            r_mid = first[min(kend >> 6, nkb)];
+            re = rows_total(rs, gm, bh);  // clamped like the entries of `first`: device data
+            rb = min(max(first[k0 >> 6], 0), re);
+            r_mid = min(max(first[min(kend >> 6, nkb)], rb), re);
         }
         if (kend > gm.T) r_mid = re;  // keys past the end of the sequence: mask everywhere
         if (re <= rb) return;

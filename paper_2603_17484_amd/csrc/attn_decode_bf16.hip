@@ -4,16 +4,17 @@
 // as o = s + d a (Sec. 3.1 Eq. 5).  HBM-bound: the cache is read once per branch that runs.
 //
 // Split-key scheme, two launches:
-//   decode_partial_kernel  grid (key chunks of 512-2048, branch, batch x KV head).  The G query heads
-//       of a KV group are the rows of one 32-row matrix tile (rows >= G are padding), so K and V
-//       are read once for all of them.  Each wavefront takes 32-key sub-blocks of the chunk: K and
-//       V rows go global -> LDS with direct loads (one 16 KB buffer per wavefront, so that two
-//       workgroups fit a CU and their eight wavefronts overlap each other's loads: that keeps
-//       more bytes in flight than double buffers in one workgroup), S^T = K Q^T and
-//       O^T += V^T P^T run on the matrix cores with
-//       the streaming softmax of App. C Alg. 1 in between; V^T operands are transposed on the way
-//       out of LDS (ds_read_b64_tr_b16).  The four wavefronts' partial (max, sum, O) are merged in
-//       LDS and written once per chunk.
+//   decode_partial_kernel  grid (chunks of 512 keys, branch, batch x KV head), one wavefront per
+//       workgroup.  The G query heads of a KV group are the rows of one 32-row matrix tile (rows >= G
+//       are padding), so K and V are read once for all of them.  The wavefront walks its chunk in
+//       32-key sub-blocks: K and V rows go global -> LDS with direct loads into its one 16 KB buffer,
+//       S^T = K Q^T and O^T += V^T P^T run on the matrix cores with the streaming softmax of App. C
+//       Alg. 1 in between; V^T operands are transposed on the way out of LDS (ds_read_b64_tr_b16).
+//       A wavefront does not overlap its own loads with its arithmetic: up to ten such workgroups
+//       share a CU and overlap each other's, which keeps 160 KB of loads in flight per CU (measured
+//       faster than double buffers in fewer, larger workgroups) and makes the units of work small
+//       enough that a mix of routed and unrouted sequences still fills the chip evenly.
+//       One partial (max, sum, O) per chunk, head and branch.
 //   decode_combine_kernel  one workgroup per (batch, query head): merges the chunks of each
 //       branch, writes S, A, the log-sum-exps and O = S + d A.
 #include "tiles.hpp"
@@ -21,8 +22,9 @@
 namespace l2a {
 namespace {
 
-constexpr int kMinChunk = 512;  // keys per workgroup: 512, 1024 or 2048, chosen per launch
+constexpr int kChunk = 512;   // keys per workgroup
 constexpr int kSub = 32;     // keys per wavefront step
+constexpr int kWaves = 1;     // wavefronts per workgroup
 constexpr int kBufs = 1;     // LDS buffers per wavefront (1: two workgroups per CU overlap each other's loads)
 constexpr int kPart = kD + 4;  // floats per partial: max (log2 units), sum, 2 unused, O[128]
 
@@ -68,9 +70,9 @@ __device__ __forceinline__ bf16x8 v_transposed_operand(const __bf16* tile, int d
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v1, v2, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-__global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64 * kWaves) void decode_partial_kernel(DecodeArgs a) {
     // per wavefront: kBufs buffers of (K tile, V tile), 32 keys x 128 channels each
-    __shared__ __attribute__((aligned(1024))) __bf16 lds[4][kBufs][2][kSub * 128];
+    __shared__ __attribute__((aligned(1024))) __bf16 lds[kWaves][kBufs][2][kSub * 128];
 
     const Geom& gm = a.gm;
     const int bh = blockIdx.z, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
@@ -136,10 +138,10 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) 
     // this wavefront's sub-blocks: kb + wave, kb + wave + 4, ...
     int sb = kb + wave;
     if (kBufs == 2 && sb <= ke) load(sb, 0);
-    for (int it = 0; sb <= ke; sb += 4, ++it) {
+    for (int it = 0; sb <= ke; sb += kWaves, ++it) {
         const int buf = kBufs == 2 ? (it & 1) : 0;
-        if (kBufs == 2 && sb + 4 <= ke) {
-            load(sb + 4, buf ^ 1);
+        if (kBufs == 2 && sb + kWaves <= ke) {
+            load(sb + kWaves, buf ^ 1);
             asm volatile("s_waitcnt vmcnt(16)" ::: "memory");  // the 16 loads just issued may stay in flight
         } else {
             if (kBufs == 1) load(sb, 0);  // the previous step's LDS reads have all returned (their MFMAs were issued)
@@ -209,12 +211,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) 
             for (int r = 0; r < 16; ++r) dst[4 + d * 32 + c_row(r, h)] = oacc[d][r];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < gm.G * kD; idx += kThreads) {
+    for (int idx = threadIdx.x; idx < gm.G * kD; idx += 64 * kWaves) {
         const int g = idx / kD, c = idx - g * kD;
         float mm = -INFINITY;
-        for (int w = 0; w < 4; ++w) mm = fmaxf(mm, stage[((size_t)w * gm.G + g) * kPart]);
+        for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, stage[((size_t)w * gm.G + g) * kPart]);
         float ll = 0.f, oo = 0.f;
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < kWaves; ++w) {
             const float* src = stage + ((size_t)w * gm.G + g) * kPart;
             const float sc = src[0] == -INFINITY ? 0.f : fast_exp2(src[0] - mm);
             ll += src[1] * sc;
@@ -229,13 +231,15 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(DecodeArgs a) 
     }
 }
 
-// 256 threads: thread = (channel, half); the two halves take alternate chunks with a running
-// maximum (loads of successive chunks are independent, the loop is unrolled) and meet in LDS.
-__global__ __launch_bounds__(2 * kD) void decode_combine_kernel(DecodeArgs a) {
-    __shared__ float sm[2][kD], sl[2][kD], so[2][kD];
+// Thread = (channel, slice): slice i of n (n = blockDim.x / 128 <= kSlices) takes every n-th chunk with a
+// running maximum (loads of successive chunks are independent, the loop is unrolled); the slices meet in LDS.
+constexpr int kSlices = 8;
+__global__ __launch_bounds__(kSlices * kD) void decode_combine_kernel(DecodeArgs a) {
+    const int nslices = blockDim.x >> 7;
+    __shared__ float sm[kSlices][kD], sl[kSlices][kD], so[kSlices][kD];
     const Geom& gm = a.gm;
     const int bhq = blockIdx.x, b = bhq / gm.Hq, head = bhq - b * gm.Hq;
-    const int c = threadIdx.x & (kD - 1), half = threadIdx.x >> 7;
+    const int c = threadIdx.x & (kD - 1), slice = threadIdx.x >> 7;
     const int t = min(max(a.pos[b], 0), gm.T - 1);
     float out[2] = {0.f, 0.f};
     float lse[2] = {-INFINITY, -INFINITY};
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(2 * kD) void decode_combine_kernel(DecodeArgs a) {
         const float* base = a.part + (((size_t)bhq * 2 + branch) * a.nchunks) * kPart;
         float mm = -INFINITY, ll = 0.f, oo = 0.f;
 #pragma unroll 8
-        for (int ch = c_lo + half; ch <= c_hi; ch += 2) {
+        for (int ch = c_lo + slice; ch <= c_hi; ch += nslices) {
             const float* src = base + (size_t)ch * kPart;
             const float m1 = src[0], l1 = src[1], o1 = src[4 + c];
             const float mn = fmaxf(mm, m1);
@@ -257,16 +261,22 @@ __global__ __launch_bounds__(2 * kD) void decode_combine_kernel(DecodeArgs a) {
             mm = mn;
         }
         __syncthreads();
-        sm[half][c] = mm, sl[half][c] = ll, so[half][c] = oo;
+        sm[slice][c] = mm, sl[slice][c] = ll, so[slice][c] = oo;
         __syncthreads();
-        const float m0 = sm[0][c], m1 = sm[1][c];  // half 1 may have had no chunk: -inf, 0, 0
-        const float mn = fmaxf(m0, m1);
-        const float s0 = fast_exp2(m0 - mn), s1 = m1 == -INFINITY ? 0.f : fast_exp2(m1 - mn);
-        const float lsum = sl[0][c] * s0 + sl[1][c] * s1;
-        out[branch] = (so[0][c] * s0 + so[1][c] * s1) / lsum;
-        lse[branch] = (mn + __builtin_amdgcn_logf(lsum)) * kLn2;
+        if (slice == 0) {  // slices that had no chunk hold (-inf, 0, 0); slice 0 always has one
+            float mn = sm[0][c];
+            for (int i = 1; i < nslices; ++i) mn = fmaxf(mn, sm[i][c]);
+            float lsum = 0.f, osum = 0.f;
+            for (int i = 0; i < nslices; ++i) {
+                const float sc = sm[i][c] == -INFINITY ? 0.f : fast_exp2(sm[i][c] - mn);
+                lsum += sl[i][c] * sc;
+                osum += so[i][c] * sc;
+            }
+            out[branch] = osum / lsum;
+            lse[branch] = (mn + __builtin_amdgcn_logf(lsum)) * kLn2;
+        }
     }
-    if (half) return;
+    if (slice) return;
     const size_t o = (size_t)bhq * kD + c;
     a.O[o] = (__bf16)(out[0] + out[1]);
     if (a.S) a.S[o] = (__bf16)out[0];
@@ -280,14 +290,14 @@ __global__ __launch_bounds__(2 * kD) void decode_combine_kernel(DecodeArgs a) {
 }  // namespace
 
 size_t decode_partial_floats(const Geom& g) {
-    const int nchunks = (g.T + kMinChunk - 1) / kMinChunk;
+    const int nchunks = (g.T + kChunk - 1) / kChunk;
     return (size_t)g.B * g.Hq * 2 * nchunks * kPart;
 }
 
 int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, const int32_t* pos, const uint8_t* mask,
                 int mask_heads, int do_local, int do_global, float* part, void* O, void* S, void* A, float* lse_l,
                 float* lse_g, hipStream_t st) {
-    if (g.D != kD || g.G > 32) return L2A_ERR_UNSUPPORTED;
+    if (g.D != kD || g.G > 16) return L2A_ERR_UNSUPPORTED;  // the merge stage holds kWaves x G partials in LDS
     DecodeArgs a{};
     a.gm = g;
     a.q = (const __bf16*)q;
@@ -299,13 +309,7 @@ int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, cons
     a.do_local = do_local;
     a.do_global = do_global;
     a.part = part;
-    // long chunks amortise a workgroup's start-up latency; short ones keep every CU busy
-    a.chunk = kMinChunk;
-    for (int c = 4 * kMinChunk; c > kMinChunk; c /= 2)
-        if ((long long)g.B * g.Hkv * ((g.T + c - 1) / c) >= 1024) {
-            a.chunk = c;
-            break;
-        }
+    a.chunk = kChunk;
     a.nchunks = (g.T + a.chunk - 1) / a.chunk;
     a.O = (__bf16*)O;
     a.S = (__bf16*)S;
@@ -314,11 +318,12 @@ int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, cons
     a.lse_g = lse_g;
     {
         KernelTimer kt("decode_partial", st);
-        hipLaunchKernelGGL(decode_partial_kernel, dim3(a.nchunks, 2, g.B * g.Hkv), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL(decode_partial_kernel, dim3(a.nchunks, 2, g.B * g.Hkv), dim3(64 * kWaves), 0, st, a);
     }
     {
         KernelTimer kt("decode_combine", st);
-        hipLaunchKernelGGL(decode_combine_kernel, dim3(g.B * g.Hq), dim3(2 * kD), 0, st, a);
+        const int slices = a.nchunks >= 128 ? 8 : (a.nchunks >= 32 ? 4 : 2);  // few chunks: few, short loops
+        hipLaunchKernelGGL(decode_combine_kernel, dim3(g.B * g.Hq), dim3(slices * kD), 0, st, a);
     }
     return launch_status();
 }

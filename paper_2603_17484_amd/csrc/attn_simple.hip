@@ -33,12 +33,12 @@ struct Row {
     int pos, g;
 };
 
-// rows of one (b, KV head): how many, and the r-th one
+// rows of one (b, KV head): how many, and the r-th one (device data: clamped into the valid ranges)
 __device__ __forceinline__ int num_rows(const RowSet& rs, const Geom& gm, int bh) {
-    return rs.count ? rs.count[bh] : gm.T * gm.G;
+    return rs.count ? min(max(rs.count[bh], 0), gm.T * gm.G) : gm.T * gm.G;
 }
 __device__ __forceinline__ Row get_row(const RowSet& rs, const Geom& gm, int bh, int r) {
-    const int code = rs.row_idx ? rs.row_idx[(size_t)bh * gm.T * gm.G + r] : r;
+    const int code = rs.row_idx ? min(max(rs.row_idx[(size_t)bh * gm.T * gm.G + r], 0), gm.T * gm.G - 1) : r;
     Row x;
     x.pos = code / gm.G;
     x.g = code - x.pos * gm.G;
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_dkdv_kernel(Geom gm, Dkdv
             r0 = j * gm.G;
             r1 = (last + 1) * gm.G;
         } else {
-            r0 = rs.kblk_first_row ? rs.kblk_first_row[(size_t)bh * (nkb + 1) + (j >> 6)] : (j >> 6) * 64 * gm.G;
+            r0 = rs.kblk_first_row ? max(rs.kblk_first_row[(size_t)bh * (nkb + 1) + (j >> 6)], 0) : (j >> 6) * 64 * gm.G;
             r1 = num_rows(rs, gm, bh);
         }
         for (int r = r0; r < r1; ++r) {

@@ -121,13 +121,15 @@ __device__ __forceinline__ bf16x8 lds_transposed(const __bf16* lds, int ch, int 
 }
 
 // ---------------------------------------------------------------------------------------
-// rows of a branch
+// rows of a branch.  The lists live in device memory, where the host cannot check them: counts and
+// row codes are clamped into their valid ranges, so that a damaged list gives wrong numbers but
+// never an address outside the tensors.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int rows_total(const RowSet& rs, const Geom& gm, int bh) {
-    return rs.count ? rs.count[bh] : gm.T * gm.G;
+    return rs.count ? min(max(rs.count[bh], 0), gm.T * gm.G) : gm.T * gm.G;
 }
 __device__ __forceinline__ int row_code(const RowSet& rs, const Geom& gm, int bh, int r) {
-    return rs.row_idx ? rs.row_idx[(size_t)bh * gm.T * gm.G + r] : r;
+    return rs.row_idx ? min(max(rs.row_idx[(size_t)bh * gm.T * gm.G + r], 0), gm.T * gm.G - 1) : r;
 }
 
 // Value of an accumulator element that lives in an AGPR (the VALU cannot read AGPRs).  Written
