@@ -27,6 +27,7 @@ constexpr int kRT = 32;     // rows per tile
 constexpr int kAhead = 3;   // operand look-ahead, in slots
 constexpr int kNB = 4;              // LDS buffers per tile kind: loads run kNB - 1 tiles ahead
 constexpr int kDmaPerStep = 11;     // direct-to-LDS instructions a wavefront issues per tile step
+constexpr int kLoadSlot0 = 16;      // they are issued in slots kLoadSlot0 .. kLoadSlot0 + 10 of a step
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -167,41 +168,80 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         return r < n ? r : 0;  // ranges that do not overlap share nothing
     };
     const int rot0 = rotation(0, tb0, n0), rot1 = rotation(1, tb1, n1);
-    auto locate = [&](int it, int& s, int& t) __attribute__((always_inline)) {
-        s = it < n0 ? 0 : 1;
-        const int j = s ? it - n0 : it, n = s ? n1 : n0, rot = s ? rot1 : rot0;
-        const int tb = s ? tb1 : tb0, te = s ? te1 : te0;
-        const int jr = j + rot >= n ? j + rot - n : j + rot;
-        t = (s ? rev1 : rev0) ? te - 1 - j : tb + jr;
+    // Loads walk the tiles with a cursor that is advanced once per step: tile te - 1 - j for a reversed
+    // set, tb + (j + rot) mod n otherwise; after the last tile of set 0 it moves on to set 1.  Past the
+    // very last tile it stays there: the steps near the end re-load that tile into buffers nobody reads
+    // any more, so that every step issues the same number of loads.
+    struct Cursor {
+        int t, left, tb, te, i;  // tile; tiles left in the set; the set's range (for the wrap); flat index
+        bool rev;
+        long long set;           // byte offset of the set's arrays
+    };
+    auto cursor_begin = [&]() __attribute__((always_inline)) {
+        Cursor c;
+        c.i = 0;
+        if (n0 > 0) {
+            c.left = n0, c.tb = tb0, c.te = te0, c.rev = rev0, c.set = 0;
+            c.t = rev0 ? te0 - 1 : tb0 + rot0;
+        } else {
+            c.left = n1, c.tb = tb1, c.te = te1, c.rev = rev1, c.set = a.set_stride;
+            c.t = rev1 ? te1 - 1 : tb1 + rot1;
+        }
+        return c;
+    };
+    const int t_set1 = rev1 ? te1 - 1 : tb1 + rot1;
+    auto advance = [&](Cursor& c) __attribute__((always_inline)) {  // branch-free: it runs between matrix instructions
+        const bool more = c.i + 1 < total;
+        const bool sw = more && c.left == 1;  // only set 0 can end before the last tile
+        int t1 = c.rev ? c.t - 1 : c.t + 1;
+        t1 = (!c.rev && t1 == c.te) ? c.tb : t1;
+        c.t = sw ? t_set1 : (more ? t1 : c.t);
+        c.left = sw ? n1 : (more ? c.left - 1 : c.left);
+        c.tb = sw ? tb1 : c.tb;
+        c.te = sw ? te1 : c.te;
+        c.rev = sw ? rev1 : c.rev;
+        c.set = sw ? a.set_stride : c.set;
+        c.i = more ? c.i + 1 : c.i;
     };
     // Every load is a wave-uniform base plus a per-lane offset fixed for the whole kernel.
     const RmDma<kRT> rm_off = rm_dma_setup<kRT>(kD * 2, wave);
     const TmDma<kRT> tm_off = tm_dma_setup<kRT>((unsigned)a.cap * 2u, wave);
     const unsigned stat_off = n * 4;
     const size_t rows_bh = (size_t)bh * a.cap;
-    auto load_rm = [&](int it, int buf) __attribute__((always_inline)) {
-        int s, t;
-        locate(it, s, t);
-        const size_t row0 = rows_bh + (size_t)t * kRT;
-        const size_t base = (size_t)s * a.set_stride + row0 * (kD * 2);
-        const unsigned dst = lds_rm0 + buf * (unsigned)sizeof(RowTileLds);
-        rm_dma_issue(rm_off, a.rows.qc + base, dst, wave);
-        rm_dma_issue(rm_off, a.rows.gc + base, dst + kRT * 256, wave);
-        // per-row statistics: 32 rows, the upper half-wave repeats the lower one (every wavefront
-        // issues them, identically, so that all wavefronts have the same number of loads in flight)
-        dma4_so(a.rows.ndelta + (size_t)s * a.set_stride + row0 * 4, stat_off, dst + 2 * kRT * 256);
+    // The 11 loads of a step (5 for a row-major tile, 6 for a token-minor tile), numbered so that the
+    // tile steps can issue them one at a time between matrix instructions.
+    struct StepLoads {
+        size_t rm256, rm4, tm2, tm4;  // byte offsets of the tiles inside the packed arrays
+        unsigned dst_rm, dst_tm;      // LDS buffers
     };
-    auto load_tm = [&](int it, int buf) __attribute__((always_inline)) {
-        int s, t;
-        locate(it, s, t);
-        const size_t set = (size_t)s * a.set_stride;
-        const size_t base = set + (rows_bh * kD + (size_t)t * kRT) * 2;
-        const size_t so = set + (rows_bh + (size_t)t * kRT) * 4;
-        const unsigned dst = lds_tm0 + buf * (unsigned)sizeof(ColTileLds);
-        tm_dma_issue(tm_off, a.rows.qt + base, dst, wave);
-        tm_dma_issue(tm_off, a.rows.gt + base, dst + kD * kRT * 2, wave);
-        dma4_so(a.rows.lse2 + so, stat_off, dst + 2 * kD * kRT * 2);
-        dma4_so(a.rows.pos + so, stat_off, dst + 2 * kD * kRT * 2 + 256);
+    auto stage_rm = [&](StepLoads& L, long long cset, int ct, int buf) __attribute__((always_inline)) {
+        const size_t set = (size_t)cset, row0 = rows_bh + (size_t)ct * kRT;
+        L.rm256 = set + row0 * (kD * 2);
+        L.rm4 = set + row0 * 4;
+        L.dst_rm = __builtin_amdgcn_readfirstlane(lds_rm0 + buf * (unsigned)sizeof(RowTileLds));
+    };
+    auto stage_tm = [&](StepLoads& L, long long cset, int ct, int buf) __attribute__((always_inline)) {
+        const size_t set = (size_t)cset;
+        L.tm2 = set + (rows_bh * kD + (size_t)ct * kRT) * 2;
+        L.tm4 = set + (rows_bh + (size_t)ct * kRT) * 4;
+        L.dst_tm = __builtin_amdgcn_readfirstlane(lds_tm0 + buf * (unsigned)sizeof(ColTileLds));
+    };
+    auto issue_load = [&](const StepLoads& L, auto kc) __attribute__((always_inline)) {
+        constexpr int k = decltype(kc)::value;
+        if constexpr (k < 5) {
+            // per-row statistics (k = 4): 32 rows, the upper half-wave repeats the lower one (every
+            // wavefront issues them, identically, so that all have the same number of loads in flight)
+            if constexpr (k < 2) dma16_so(a.rows.qc + L.rm256, rm_off.voff[k], L.dst_rm + (k * 4 + wave) * 1024);
+            else if constexpr (k < 4)
+                dma16_so(a.rows.gc + L.rm256, rm_off.voff[k - 2], L.dst_rm + kRT * 256 + ((k - 2) * 4 + wave) * 1024);
+            else dma4_so(a.rows.ndelta + L.rm4, stat_off, L.dst_rm + 2 * kRT * 256);
+        } else {
+            if constexpr (k < 7) dma16_so(a.rows.qt + L.tm2, tm_off.voff[k - 5], L.dst_tm + ((k - 5) * 4 + wave) * 1024);
+            else if constexpr (k < 9)
+                dma16_so(a.rows.gt + L.tm2, tm_off.voff[k - 7], L.dst_tm + kD * kRT * 2 + ((k - 7) * 4 + wave) * 1024);
+            else if constexpr (k == 9) dma4_so(a.rows.lse2 + L.tm4, stat_off, L.dst_tm + 2 * kD * kRT * 2);
+            else dma4_so(a.rows.pos + L.tm4, stat_off, L.dst_tm + 2 * kD * kRT * 2 + 256);
+        }
     };
 
     f32x16 dkacc[4], dvacc[4];
@@ -216,8 +256,9 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
 
     // One tile: P, dS from `cur` (tile it; statistics and token-minor tiles in ct) overlapped with
     // S, dP of tile it+1 into `nxt` (row-major tiles rt) and the dV, dK update of tile it.
-    auto tile_step = [&](auto mask_tag, SdP& cur, SdP& nxt, const RowTileLds& rt, const ColTileLds& ct, bool local)
-                         __attribute__((always_inline)) {
+    auto tile_step = [&](auto mask_tag, SdP& cur, SdP& nxt, const RowTileLds& rt, const ColTileLds& ct, bool local,
+                         auto&& stage_loads, auto&& loads_issued) __attribute__((always_inline)) {
+        StepLoads L;
         constexpr bool MASK = decltype(mask_tag)::value;
         const float c2 = gm.scale_log2;
         bf16x8 opnd[32 + kAhead];
@@ -298,6 +339,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 constexpr int q = decltype(qc)::value;
                 if constexpr ((q * 7) / 4 == mm) ds_pair(qc);
             });
+            // the loads of later tiles go out one per slot where the VALU has nothing to do
+            if constexpr (mm == kLoadSlot0 - 1) stage_loads(L);
+            if constexpr (mm == kLoadSlot0 + kDmaPerStep) loads_issued();
+            if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + kDmaPerStep) issue_load(L, Int<mm - kLoadSlot0>{});
             L2A_FENCE();
         });
     };
@@ -305,12 +350,21 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     if (total > 0) {
         // ---- prologue: row-major tiles 0 and 1, token-minor tile 0; S, dP of tile 0
         SdP Xa, Xb;
-#pragma unroll
-        for (int i = 0; i < kNB; ++i)
-            if (i < total) load_rm(i, i);
-#pragma unroll
-        for (int i = 0; i < kNB - 1; ++i)
-            if (i < total) load_tm(i, i);
+        // The token-minor loads run one tile behind the row-major ones: they use the cursor's last position.
+        Cursor lc = cursor_begin();
+        long long tm_set = lc.set;
+        int tm_t = lc.t;
+        static_for<0, kNB>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            StepLoads L;
+            stage_rm(L, lc.set, lc.t, i);
+            stage_tm(L, lc.set, lc.t, i);
+            static_for<0, kDmaPerStep>([&](auto kc) {
+                if constexpr (decltype(kc)::value < 5 || i < kNB - 1) issue_load(L, kc);
+            });
+            tm_set = lc.set, tm_t = lc.t;
+            advance(lc);
+        });
         dma_wait();
         __syncthreads();
 #pragma unroll
@@ -324,18 +378,23 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         }
         mfma_vgpr_settle();  // the first tile step reads Xa at once
 
-        // Step `it` reads the row-major tile it+1 and the token-minor tile it, and starts the loads
-        // of row-major tile it+kNB (into the buffer tile `it` left one step ago) and token-minor tile
-        // it+kNB-1 (buffer of tile it-1).  At its end only the loads of the last kNB-2 steps may
-        // still be in flight.  Two tiles per trip so that the two S/dP buffers swap roles without copies.
+        // Step `it` reads the row-major tile it+1 and the token-minor tile it, and in its second half
+        // issues the loads of row-major tile it+kNB (into the buffer tile `it` left one step ago) and
+        // token-minor tile it+kNB-1 (buffer of tile it-1).  At its end only the loads of the last
+        // kNB-2 steps may still be in flight.  Two tiles per trip so that the two S/dP buffers swap
+        // roles without copies.
         auto one = [&](auto mask_tag, SdP& cur, SdP& nxt, int it, bool local) __attribute__((always_inline)) {
-            if (it + kNB < total) load_rm(it + kNB, it % kNB);
-            if (it + kNB - 1 < total) load_tm(it + kNB - 1, (it + kNB - 1) % kNB);
-            tile_step(mask_tag, cur, nxt, lds_rm[(it + 1) % kNB], lds_tm[it % kNB], local);
-            if (it + kNB < total)
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kNB - 2) * kDmaPerStep) : "memory");
-            else
-                dma_wait();
+            static_assert((kNB & (kNB - 1)) == 0, "buffer indices are taken with a mask");
+            tile_step(mask_tag, cur, nxt, lds_rm[(it + 1) & (kNB - 1)], lds_tm[it & (kNB - 1)], local,
+                      [&](StepLoads& L) __attribute__((always_inline)) {
+                          stage_rm(L, lc.set, lc.t, it & (kNB - 1));
+                          stage_tm(L, tm_set, tm_t, (it + kNB - 1) & (kNB - 1));
+                      },
+                      [&]() __attribute__((always_inline)) {
+                          tm_set = lc.set, tm_t = lc.t;
+                          advance(lc);
+                      });
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kNB - 2) * kDmaPerStep) : "memory");
             __syncthreads();
         };
         // The two S/dP buffers swap roles every tile; which one holds the current tile is carried
@@ -384,6 +443,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             walk(s, sb + rot, se, local);     // a reversed set has no rotation: the whole range
             if (rot) walk(s, sb, sb + rot, local);
         }
+        dma_wait();  // the last steps' loads (re-loads of the last tile) must land before the LDS is given up
     }
 
     // ---- write dK, dV: lane = channel d*32+n, register e = key c_row(e, h)
