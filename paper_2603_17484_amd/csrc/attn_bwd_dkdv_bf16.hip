@@ -27,7 +27,8 @@ constexpr int kRT = 32;     // rows per tile
 constexpr int kAhead = 3;   // operand look-ahead, in slots
 constexpr int kNB = 4;              // LDS buffers per tile kind: loads run kNB - 1 tiles ahead
 constexpr int kDmaPerStep = 11;     // direct-to-LDS instructions a wavefront issues per tile step
-constexpr int kLoadSlot0 = 16;      // they are issued in slots kLoadSlot0 .. kLoadSlot0 + 10 of a step
+constexpr int kLoadSlot0 = 1;       // ... in slots kLoadSlot0 + kLoadStride i of a step, i = 0 .. 10: the four wavefronts
+constexpr int kLoadStride = 3;      // issue theirs at about the same time, and the load path takes them one by one
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -339,10 +340,12 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 constexpr int q = decltype(qc)::value;
                 if constexpr ((q * 7) / 4 == mm) ds_pair(qc);
             });
-            // the loads of later tiles go out one per slot where the VALU has nothing to do
+            // the loads of later tiles go out spread over the step
             if constexpr (mm == kLoadSlot0 - 1) stage_loads(L);
-            if constexpr (mm == kLoadSlot0 + kDmaPerStep) loads_issued();
-            if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + kDmaPerStep) issue_load(L, Int<mm - kLoadSlot0>{});
+            if constexpr (mm >= kLoadSlot0 && (mm - kLoadSlot0) % kLoadStride == 0 &&
+                          (mm - kLoadSlot0) / kLoadStride < kDmaPerStep)
+                issue_load(L, Int<(mm - kLoadSlot0) / kLoadStride>{});
+            if constexpr (mm == kLoadSlot0 + kLoadStride * (kDmaPerStep - 1)) loads_issued();
             L2A_FENCE();
         });
     };

@@ -32,6 +32,7 @@ constexpr int kNQB = 2;  // 32-row blocks per wavefront
 constexpr int kRW = 32 * kNQB;
 constexpr int kBQ = 4 * kRW;
 constexpr int kAhead = 2;  // operand look-ahead, in operands (each feeds two instructions)
+constexpr int kLoadSlot0 = 23;  // the loads of later blocks go out in slots 23-30 of a block's first half
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -118,6 +119,27 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     auto load_v = [&](int jb, int buf) __attribute__((always_inline)) {
         tm_dma_issue(v_off, vtbase + (size_t)jb * kBK * 2, lds_v0 + buf * (kD * kBK * 2), wave);
     };
+    // In the main loop the eight loads of a block are issued one at a time between matrix
+    // instructions.  K rows are clamped to the end of the sequence on the fly (rows past it are always
+    // masked), so that the ragged last block needs no code path of its own:
+    // lane l of load i fetches chunk (l & 15) ^ (row & 15) of row (4 i + wave) * 4 + (l >> 4).
+    const int k_lane_row = wave * 4 + (lane >> 4);
+    const unsigned k_lane_chunk = (unsigned)(((lane & 15) ^ (k_lane_row & 15)) * 16);
+    struct BlockLoads {
+        const char* ksrc;
+        const char* vsrc;
+        unsigned kdst, vdst;
+        int krows;  // rows of the K block that exist
+    };
+    auto issue_block_load = [&](const BlockLoads& L, auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i < 4) {
+            const unsigned row = (unsigned)min(k_lane_row + 16 * i, L.krows - 1);
+            dma16_so(L.ksrc, __umul24(row, kv_row_bytes) + k_lane_chunk, L.kdst + (i * 4 + wave) * 1024);
+        } else {
+            dma16_so(L.vsrc, v_off.voff[i - 4], L.vdst + ((i - 4) * 4 + wave) * 1024);
+        }
+    };
 
     f32x16 oacc[4][kNQB];
     float mref[kNQB], negm[kNQB], l[kNQB];
@@ -143,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     //   slots  0-15  next half-block's scores | exp, row sum, pack P  (pair q in slot 3 q / 2)
     //   slots 16-31  O += P V
     auto half_block = [&](auto mask_tag, auto kb_tag, Scores& cur, Scores& nxt, const __bf16* kt, int krow0,
-                          const __bf16* vt, int k0) __attribute__((always_inline)) {
+                          const __bf16* vt, int k0, auto&& side) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         constexpr int KB = decltype(kb_tag)::value;
         const float c2 = gm.scale_log2;
@@ -198,6 +220,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
                 constexpr int q = decltype(qc)::value;
                 if constexpr ((3 * q) / 2 == mm) exp_pair(qc);
             });
+            side(mc);
             L2A_FENCE();
         });
 #pragma unroll
@@ -261,13 +284,25 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
         for (int jb = j_begin; jb < j_end; ++jb) {
             const int rel = jb - jb0;
             const int kbuf = rel % 3, kbuf1 = (rel + 1) % 3, kbuf2 = (rel + 2) % 3;
-            // prefetch: K of block jb+2 (its buffer held block jb-1), V of block jb+1 (held block jb-1)
-            if (jb + 2 <= jb1) load_k(jb + 2, kbuf2);
-            if (jb + 1 <= jb1) load_v(jb + 1, (rel + 1) & 1);
+            // prefetch: K of block jb+2 (its buffer held block jb-1), V of block jb+1 (held block jb-1),
+            // issued in the slots of the first half-block where the VALU has nothing to do.  Past the
+            // last block the last one is loaded again, into buffers nobody reads any more.
+            const int jk = min(jb + 2, jb1), jv = min(jb + 1, jb1);
             {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
                 const __bf16* vt = &lds_v[rel & 1][0];
-                half_block(mask_tag, Int<0>{}, Sa, Sb, &lds_k[kbuf][0], 32, vt, jb * kBK);
-                half_block(mask_tag, Int<1>{}, Sb, Sa, &lds_k[kbuf1][0], 0, vt, jb * kBK + 32);
+                BlockLoads L;
+                half_block(mask_tag, Int<0>{}, Sa, Sb, &lds_k[kbuf][0], 32, vt, jb * kBK, [&](auto mc) {
+                    constexpr int mm = decltype(mc)::value;
+                    if constexpr (mm == kLoadSlot0 - 1) {
+                        L.ksrc = kbase + (size_t)jk * kBK * kv_row_bytes;
+                        L.vsrc = vtbase + (size_t)jv * kBK * 2;
+                        L.kdst = lds_k0 + kbuf2 * (kBK * 256);
+                        L.vdst = lds_v0 + ((rel + 1) & 1) * (kD * kBK * 2);
+                        L.krows = min(kBK, gm.T - jk * kBK);
+                    }
+                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 8) issue_block_load(L, Int<mm - kLoadSlot0>{});
+                });
+                half_block(mask_tag, Int<1>{}, Sb, Sa, &lds_k[kbuf1][0], 0, vt, jb * kBK + 32, [](auto) {});
             }
             dma_wait();
             __syncthreads();
