@@ -23,6 +23,7 @@ constexpr int kBK = 64;
 constexpr int kRW = 32;        // rows per wavefront
 constexpr int kBQ = 4 * kRW;   // rows per workgroup
 constexpr int kAhead = 3;      // operand look-ahead, in slots
+constexpr int kLoadSlot0 = 12;  // the loads of later blocks go out in slots 12-23 of a block's first half
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -126,6 +127,30 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     auto load_kt = [&](int jb, int buf) __attribute__((always_inline)) {
         tm_dma_issue(kt_off, ktbase + (size_t)jb * kBK * 2, lds_kt0 + buf * (kD * kBK * 2), wave);
     };
+    // In the main loop the twelve loads of a block are issued one at a time between matrix
+    // instructions.  K and V rows are clamped to the end of the sequence on the fly (rows past it are
+    // always masked), so that the ragged last block needs no code path of its own:
+    // lane l of load i fetches chunk (l & 15) ^ (row & 15) of row (4 i + wave) * 4 + (l >> 4).
+    const int k_lane_row = wave * 4 + (lane >> 4);
+    const unsigned k_lane_chunk = (unsigned)(((lane & 15) ^ (k_lane_row & 15)) * 16);
+    struct BlockLoads {
+        const char* ksrc;
+        const char* vsrc;
+        const char* ktsrc;
+        unsigned kdst, vdst, ktdst;
+        int krows;  // rows of the K, V block that exist
+    };
+    auto issue_block_load = [&](const BlockLoads& L, auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i < 8) {
+            const unsigned row = (unsigned)min(k_lane_row + 16 * (i & 3), L.krows - 1);
+            const unsigned voff = __umul24(row, kv_row_bytes) + k_lane_chunk;
+            if constexpr (i < 4) dma16_so(L.ksrc, voff, L.kdst + (i * 4 + wave) * 1024);
+            else dma16_so(L.vsrc, voff, L.vdst + ((i - 4) * 4 + wave) * 1024);
+        } else {
+            dma16_so(L.ktsrc, kt_off.voff[i - 8], L.ktdst + ((i - 8) * 4 + wave) * 1024);
+        }
+    };
 
     f32x16 acc[4];
 #pragma unroll
@@ -137,7 +162,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     // One half-block (32 keys k0..k0+31, half KB of its block): dS from `cur`, overlapped with S, dP
     // of the next half-block into `nxt` (rows krow0.. of tiles kt_, vt_) and dQ += K^T dS (tile ktt).
     auto half_block = [&](auto mask_tag, auto kb_tag, SdP& cur, SdP& nxt, const __bf16* kt_, const __bf16* vt_,
-                          int krow0, const __bf16* ktt, int k0) __attribute__((always_inline)) {
+                          int krow0, const __bf16* ktt, int k0, auto&& side) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         constexpr int KB = decltype(kb_tag)::value;
         const float c2 = gm.scale_log2;
@@ -203,6 +228,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
                 constexpr int q = decltype(qc)::value;
                 if constexpr ((q * 7) / 4 == mm) ds_pair(qc);
             });
+            side(mc);
             L2A_FENCE();
         });
         dlt_exact += dsum;
@@ -230,19 +256,39 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
         mfma_vgpr_settle();  // the first half-block reads Xa at once
     }
 
+    // K, V blocks rotate through three buffers: block jb in buf, jb+1 in buf1, and the block loaded now, jb+2, in buf2
+    int buf = 0, buf1 = 1, buf2 = 2;
     auto run = [&](auto mask_tag, int j_begin, int j_end) __attribute__((always_inline)) {
         for (int jb = j_begin; jb < j_end; ++jb) {
             const int rel = jb - jb0;
-            const int buf = rel % 3, buf1 = (rel + 1) % 3, buf2 = (rel + 2) % 3;
-            if (jb + 2 <= jb1) load_kv(jb + 2, buf2);          // that buffer held block jb-1
-            if (jb + 1 <= jb1) load_kt(jb + 1, (rel + 1) & 1);  // held block jb-1
+            // prefetch: K, V of block jb+2 (their buffer held block jb-1) and token-minor K of block jb+1
+            // (held block jb-1), issued in the slots of the first half-block where the VALU has nothing
+            // to do.  Past the last block the last one is loaded again, into buffers nobody reads any more.
+            const int jk = min(jb + 2, jb1), jt = min(jb + 1, jb1);
             {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
                 const __bf16* ktt = &lds_kt[rel & 1][0];
-                half_block(mask_tag, Int<0>{}, Xa, Xb, &lds_k[buf][0], &lds_v[buf][0], 32, ktt, jb * kBK);
-                half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], &lds_v[buf1][0], 0, ktt, jb * kBK + 32);
+                BlockLoads L;
+                half_block(mask_tag, Int<0>{}, Xa, Xb, &lds_k[buf][0], &lds_v[buf][0], 32, ktt, jb * kBK, [&](auto mc) {
+                    constexpr int mm = decltype(mc)::value;
+                    if constexpr (mm == kLoadSlot0 - 1) {
+                        const size_t src = (size_t)jk * kBK * kv_row_bytes;
+                        L.ksrc = kbase + src;
+                        L.vsrc = vbase + src;
+                        L.ktsrc = ktbase + (size_t)jt * kBK * 2;
+                        L.kdst = lds_k0 + buf2 * (kBK * 256);
+                        L.vdst = lds_v0 + buf2 * (kBK * 256);
+                        L.ktdst = lds_kt0 + ((rel + 1) & 1) * (kD * kBK * 2);
+                        L.krows = min(kBK, gm.T - jk * kBK);
+                    }
+                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 12) issue_block_load(L, Int<mm - kLoadSlot0>{});
+                });
+                half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], &lds_v[buf1][0], 0, ktt, jb * kBK + 32,
+                           [](auto) {});
             }
             dma_wait();
             __syncthreads();
+            const int t = buf;
+            buf = buf1, buf1 = buf2, buf2 = t;
         }
     };
     for (int seg = 0; seg < 3; ++seg) {

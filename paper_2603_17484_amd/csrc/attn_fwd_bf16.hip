@@ -280,10 +280,11 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     }
 
     // One block = two half-blocks; Sa holds the scores of a block's first half on entry and exit.
+    // K blocks rotate through three buffers: block jb in kbuf, jb+1 in kbuf1, and the block loaded now, jb+2, in kbuf2
+    int kbuf = 0, kbuf1 = 1, kbuf2 = 2;
     auto run = [&](auto mask_tag, int j_begin, int j_end) __attribute__((always_inline)) {
         for (int jb = j_begin; jb < j_end; ++jb) {
             const int rel = jb - jb0;
-            const int kbuf = rel % 3, kbuf1 = (rel + 1) % 3, kbuf2 = (rel + 2) % 3;
             // prefetch: K of block jb+2 (its buffer held block jb-1), V of block jb+1 (held block jb-1),
             // issued in the slots of the first half-block where the VALU has nothing to do.  Past the
             // last block the last one is loaded again, into buffers nobody reads any more.
@@ -306,6 +307,8 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
             }
             dma_wait();
             __syncthreads();
+            const int t = kbuf;
+            kbuf = kbuf1, kbuf1 = kbuf2, kbuf2 = t;
         }
     };
     // three runs: window-start masks (LOCAL), no masks, causal diagonal
