@@ -25,15 +25,21 @@ def tol_for(ref, dtype, grad):
     if dtype == "fp32":
         return np.full(ref.shape, 1e-4)
     if grad:
-        return 2e-2 + np.abs(ref) * 2.0 ** -7
+        # P and dS enter the matrix cores rounded to bf16: the error of a gradient element is a sum of
+        # rounding errors of its terms, shared by all channels of the row, and does not shrink when the
+        # terms cancel -- so it is bounded against the largest element of the row, not the element itself
+        return 2e-2 + np.abs(ref).max(axis=-1, keepdims=True) * 2.0 ** -7 + 0 * ref
     return np.maximum(2e-2, np.abs(ref) * 2.0 ** -8)
 
 
 def assert_close(name, got, ref, dtype):
     err = np.abs(got - ref)
-    bad = err > tol_for(ref, dtype, grad=name.startswith("d"))
-    assert not bad.any(), (f"{name}: {bad.sum()} of {bad.size} elements off, max err {err.max():.3e} "
-                           f"at {np.unravel_index(err.argmax(), err.shape)} (ref {ref.flat[err.argmax()]:.4f})")
+    tol = tol_for(ref, dtype, grad=name.startswith("d"))
+    bad = err > tol
+    worst = (err - tol).argmax()
+    assert not bad.any(), (f"{name}: {bad.sum()} of {bad.size} elements off; worst at {np.unravel_index(worst, err.shape)}: "
+                           f"err {err.flat[worst]:.3e} > tol {tol.flat[worst]:.3e} (ref {ref.flat[worst]:.4f}); "
+                           f"max err {err.max():.3e}")
     return float(err.max())
 
 
@@ -268,6 +274,29 @@ def test_bf16_scores_falling_along_sequence(oracle):
 def test_bf16_ragged_tiles(oracle, T, Hq, Hkv):
     """Row counts and key counts just past tile boundaries; T * G not a multiple of the row tile."""
     run_and_check(oracle, make_case(T=T, Hq=Hq, Hkv=Hkv, W=70, f=0.35, seed=50 + T % 13))
+
+
+def _random_shape(i):
+    """Seeded draw of a small layer: lengths around tile and block edges, every head layout and mask
+    granularity, windows from 0 to beyond the sequence, routed fractions from none to all."""
+    rng = np.random.default_rng(7000 + i)
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 7, 8]))
+    base = int(rng.choice([1, 31, 64, 127, 128, 256, 300, 512, 1000, 1537, 2304]))
+    T = max(1, base + int(rng.integers(-2, 3)))
+    W = int(rng.choice([0, 1, 5, 63, 64, 65, 200, 511, T - 1 if T > 1 else 0, T + 7]))
+    Hm = int(rng.choice([1, Hkv, Hkv * G]))
+    f = float(rng.choice([0.0, 0.05, 0.2, 0.5, 0.9, 1.0]))
+    Bn = int(rng.choice([1, 1, 2]))
+    return dict(B_=Bn, T=T, Hq=Hkv * G, Hkv=Hkv, W=W, Hm=Hm, f=f, seed=7100 + i)
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_bf16_random_shapes(oracle, i):
+    """Whole tensors, forward and backward, on shapes nobody picked by hand."""
+    cfg = _random_shape(i)
+    print("case", cfg, flush=True)
+    run_and_check(oracle, make_case(**cfg))
 
 
 # ------------------------------------------------------------------------------------------
