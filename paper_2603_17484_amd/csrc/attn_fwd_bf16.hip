@@ -6,10 +6,12 @@
 // The epilogue writes the log-sum-exp and merges into O (Sec. 3.1 Eq. 5), so the scatter of
 // Alg. 1's last step costs no extra pass.
 //
-// Work decomposition.  One workgroup = 4 wavefronts = a tile of 256 consecutive rows of one
-// (batch, KV head); the rows of the G query heads of the group are interleaved, so every row of
+// Work decomposition.  One workgroup = 8 wavefronts of 32 rows = a tile of 256 consecutive rows of
+// one (batch, KV head); the rows of the G query heads of the group are interleaved, so every row of
 // a tile reads the same K/V.  K and the token-minor copy of V are streamed through LDS in blocks
-// of 64 keys by direct global->LDS loads (two buffers each, one barrier per block).
+// of 64 keys by direct global->LDS loads (three and two buffers, one barrier per block).  With 32 rows
+// a wavefront needs 256 registers, so two share a SIMD (measured 2-5 % faster than 4 wavefronts of 64
+// rows at 500 registers, which the kernel template still covers).
 //
 // Everything is computed transposed so that a lane owns a query row:
 //   S^T[key, row]  = K Q^T     A = K block (LDS), B = Q (registers, loaded once)
@@ -18,21 +20,21 @@
 // and row sum are in-register reductions plus one cross-lane exchange, and rescaling O is a
 // per-lane scalar.
 //
-// Software pipeline (one wavefront per SIMD, 64 matrix-core instructions per block, issued as 64
-// slots): while block j's scores go through the softmax on the VALU, the matrix cores first
-// compute block j+1's scores (slots 0-31) and then accumulate P_j V_j (slots 32-63, in the
-// order the softmax finishes the 16-key groups).  LDS operand reads run a few slots ahead.
+// Software pipeline (per wavefront and half-block of 32 keys: 16 matrix-core instructions per 32 rows,
+// issued as numbered slots): while half-block j's scores go through the softmax on the VALU, the
+// matrix cores first compute half-block j+1's scores and then accumulate P_j V_j (in the order the
+// softmax finishes the 16-key groups).  LDS operand reads run a few slots ahead.
 #include "tiles.hpp"
 
 namespace l2a {
 namespace {
 
 constexpr int kBK = 64;  // keys per block
-constexpr int kNQB = 2;  // 32-row blocks per wavefront
+constexpr int kNQB = 2;  // 32-row blocks per wavefront (fix-up kernel)
+constexpr int kFwdNQB = 1, kFwdNW = 8;  // the pipelined kernel's shape: see fwd_kernel
 constexpr int kRW = 32 * kNQB;
 constexpr int kBQ = 4 * kRW;
 constexpr int kAhead = 2;  // operand look-ahead, in operands (each feeds two instructions)
-constexpr int kLoadSlot0 = 23;  // the loads of later blocks go out in slots 23-30 of a block's first half
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -48,15 +50,25 @@ struct FwdArgs {
     FwdOut out;
 };
 
-struct Scores {
-    f32x16 s[kNQB];  // 32 keys x (kNQB x 32) rows
+template <int NQB>
+struct ScoresT {
+    f32x16 s[NQB];  // 32 keys x (NQB x 32) rows
 };
 
 template <int V>
 using Int = std::integral_constant<int, V>;
 
-template <bool LOCAL>
-__global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
+// NW wavefronts of NQB x 32 rows each (NW * NQB = 8): 4 x 2 runs one wavefront per SIMD with 500 registers,
+// 8 x 1 runs two per SIMD with 256 each, so that one wavefront's softmax arithmetic can overlap the
+// other's matrix instructions.
+template <bool LOCAL, int NQB, int NW>
+__global__ __launch_bounds__(64 * NW) void fwd_kernel(FwdArgs a) {
+    static_assert(NW * NQB * 32 == kBQ, "a workgroup covers kBQ rows");
+    constexpr int RW = 32 * NQB;       // rows per wavefront
+    constexpr int NS = 16 * NQB;       // slots (matrix instructions) per half-block: NS / 2 for S, NS / 2 for P V
+    constexpr int NL = 16 / NW;        // 16-byte loads a wavefront issues per K or V block
+    constexpr int kLoadSlot0 = NS - 1 - 2 * NL;  // the loads of later blocks go out in the last slots of a block's first half
+    using Scores = ScoresT<NQB>;
     __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
     __shared__ __attribute__((aligned(1024))) __bf16 lds_v[2][kD * kBK];
 
@@ -75,14 +87,14 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     const int wg_r1 = min(wg_r0 + kBQ, n_rows);  // exclusive
     const int wg_pmin = row_code(a.rs, gm, bh, wg_r0) / gm.G;
     const int wg_pmax = row_code(a.rs, gm, bh, wg_r1 - 1) / gm.G;
-    const int wv_r0 = wg_r0 + wave * kRW;
+    const int wv_r0 = wg_r0 + wave * RW;
     const bool wave_active = wv_r0 < n_rows;
 
-    int pos[kNQB], head[kNQB];
-    bool valid[kNQB];
-    bf16x8 qreg[kNQB][8];
+    int pos[NQB], head[NQB];
+    bool valid[NQB];
+    bf16x8 qreg[NQB][8];
 #pragma unroll
-    for (int c = 0; c < kNQB; ++c) {
+    for (int c = 0; c < NQB; ++c) {
         const int r = wv_r0 + c * 32 + n;
         valid[c] = r < n_rows;
         // rows past the end repeat the last row: computed, never written
@@ -107,22 +119,22 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     const char* kbase = (const char*)(a.k + ((size_t)b * gm.T * gm.Hkv + hk) * kD);
     const char* vtbase = (const char*)(a.vt + (size_t)bh * kD * a.vt_cap);
     const unsigned lds_k0 = lds_offset(&lds_k[0][0]), lds_v0 = lds_offset(&lds_v[0][0]);
-    const RmDma<kBK> k_off = rm_dma_setup<kBK>(kv_row_bytes, wave);
-    const TmDma<kBK> v_off = tm_dma_setup<kBK>((unsigned)a.vt_cap * 2u, wave);
+    const RmDma<kBK, NW> k_off = rm_dma_setup<kBK, NW>(kv_row_bytes, wave);
+    const TmDma<kBK, NW> v_off = tm_dma_setup<kBK, NW>((unsigned)a.vt_cap * 2u, wave);
     auto load_k = [&](int jb, int buf) __attribute__((always_inline)) {
         const char* src = kbase + (size_t)jb * kBK * kv_row_bytes;
         const unsigned dst = lds_k0 + buf * (kBK * 256);
         if ((jb + 1) * kBK <= gm.T) rm_dma_issue(k_off, src, dst, wave);
         else  // keys past the end of the sequence are clamped: always masked, never out of bounds
-            rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, src, dst, wave);
+            rm_dma_issue_clamped<kBK, NW>(kv_row_bytes, gm.T - jb * kBK, src, dst, wave);
     };
     auto load_v = [&](int jb, int buf) __attribute__((always_inline)) {
         tm_dma_issue(v_off, vtbase + (size_t)jb * kBK * 2, lds_v0 + buf * (kD * kBK * 2), wave);
     };
-    // In the main loop the eight loads of a block are issued one at a time between matrix
+    // In the main loop the 2 NL loads of a block are issued one at a time between matrix
     // instructions.  K rows are clamped to the end of the sequence on the fly (rows past it are always
     // masked), so that the ragged last block needs no code path of its own:
-    // lane l of load i fetches chunk (l & 15) ^ (row & 15) of row (4 i + wave) * 4 + (l >> 4).
+    // lane l of load i fetches chunk (l & 15) ^ (row & 15) of row (NW i + wave) * 4 + (l >> 4).
     const int k_lane_row = wave * 4 + (lane >> 4);
     const unsigned k_lane_chunk = (unsigned)(((lane & 15) ^ (k_lane_row & 15)) * 16);
     struct BlockLoads {
@@ -133,18 +145,18 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     };
     auto issue_block_load = [&](const BlockLoads& L, auto ic) __attribute__((always_inline)) {
         constexpr int i = decltype(ic)::value;
-        if constexpr (i < 4) {
-            const unsigned row = (unsigned)min(k_lane_row + 16 * i, L.krows - 1);
-            dma16_so(L.ksrc, __umul24(row, kv_row_bytes) + k_lane_chunk, L.kdst + (i * 4 + wave) * 1024);
+        if constexpr (i < NL) {
+            const unsigned row = (unsigned)min(k_lane_row + 4 * NW * i, L.krows - 1);
+            dma16_so(L.ksrc, __umul24(row, kv_row_bytes) + k_lane_chunk, L.kdst + (i * NW + wave) * 1024);
         } else {
-            dma16_so(L.vsrc, v_off.voff[i - 4], L.vdst + ((i - 4) * 4 + wave) * 1024);
+            dma16_so(L.vsrc, v_off.voff[i - NL], L.vdst + ((i - NL) * NW + wave) * 1024);
         }
     };
 
-    f32x16 oacc[4][kNQB];
-    float mref[kNQB], negm[kNQB], l[kNQB];
+    f32x16 oacc[4][NQB];
+    float mref[NQB], negm[NQB], l[NQB];
 #pragma unroll
-    for (int c = 0; c < kNQB; ++c) {
+    for (int c = 0; c < NQB; ++c) {
         l[c] = 0.f;
 #pragma unroll
         for (int d = 0; d < 4; ++d)
@@ -162,19 +174,20 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     // row's fixed reference, overlapped with the scores of the next half-block into `nxt` (K rows
     // krow0.. of tile kt) and with O += P V for this half-block (tile vt).  32 matrix-core
     // instructions = 32 slots:
-    //   slots  0-15  next half-block's scores | exp, row sum, pack P  (pair q in slot 3 q / 2)
-    //   slots 16-31  O += P V
+    //   first half of the slots   next half-block's scores | exp, row sum, pack P  (pair q in slot 3 q / 2)
+    //   second half               O += P V
+    auto score = [&](float x) __attribute__((always_inline)) { return NQB == 2 ? acc_read(x) : x; };
     auto half_block = [&](auto mask_tag, auto kb_tag, Scores& cur, Scores& nxt, const __bf16* kt, int krow0,
                           const __bf16* vt, int k0, auto&& side) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         constexpr int KB = decltype(kb_tag)::value;
         const float c2 = gm.scale_log2;
         bf16x8 opnd[16 + kAhead];
-        uint32_t pw[kNQB][2][4];  // P as packed bf16 pairs: [row block][16-key group][dword]
-        float rsum[kNQB];
+        uint32_t pw[NQB][2][4];  // P as packed bf16 pairs: [row block][16-key group][dword]
+        float rsum[NQB];
         const bf16x2 one2 = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-        for (int c = 0; c < kNQB; ++c) rsum[c] = 0.f;
+        for (int c = 0; c < NQB; ++c) rsum[c] = 0.f;
         // operand o: o < 8 -> K rows of the next half-block (ks = o); else V^T (16-key group, channel block)
         auto read_operand = [&](auto oc) {
             constexpr int o = decltype(oc)::value;
@@ -183,21 +196,21 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
         };
         auto issue = [&](auto mc) {
             constexpr int mm = decltype(mc)::value;
-            if constexpr (mm < 16) {
-                constexpr int ks = mm >> 1, c = mm & 1;
+            if constexpr (mm < NS / 2) {
+                constexpr int ks = mm / NQB, c = mm % NQB;
                 nxt.s[c] = mfma32(opnd[ks], qreg[c][ks], ks == 0 ? zero16 : nxt.s[c]);
             } else {
-                constexpr int x = mm - 16, grp = x >> 3, d = (x >> 1) & 3, c = x & 1;
+                constexpr int x = mm - NS / 2, grp = x / (4 * NQB), d = (x / NQB) & 3, c = x % NQB;
                 const u32x4 pv = {pw[c][grp][0], pw[c][grp][1], pw[c][grp][2], pw[c][grp][3]};
-                oacc[d][c] = mfma32(opnd[8 + (x >> 1)], __builtin_bit_cast(bf16x8, pv), oacc[d][c]);
+                oacc[d][c] = mfma32(opnd[8 + x / NQB], __builtin_bit_cast(bf16x8, pv), oacc[d][c]);
             }
         };
-        // exp of one pair of scores: pair q in 0..15, in the order the P V product consumes them
+        // exp of one pair of scores: pair q in 0 .. 8 NQB - 1, in the order the P V product consumes them
         auto exp_pair = [&](auto qc) {
             constexpr int q = decltype(qc)::value;
-            constexpr int grp = q >> 3, c = (q >> 2) & 1, i2 = (q & 3) * 2, r = grp * 8 + i2;
-            float p0 = fast_exp2(fmaf(acc_read(cur.s[c][r]), c2, negm[c]));
-            float p1 = fast_exp2(fmaf(acc_read(cur.s[c][r + 1]), c2, negm[c]));
+            constexpr int grp = q / (4 * NQB), c = (q >> 2) % NQB, i2 = (q & 3) * 2, r = grp * 8 + i2;
+            float p0 = fast_exp2(fmaf(score(cur.s[c][r]), c2, negm[c]));
+            float p1 = fast_exp2(fmaf(score(cur.s[c][r + 1]), c2, negm[c]));
             if (MASK) {
                 p0 = key_ok(k0 + c_row(r, h), c) ? p0 : 0.f;
                 p1 = key_ok(k0 + c_row(r + 1, h), c) ? p1 : 0.f;
@@ -212,11 +225,11 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
 
         static_for<0, kAhead>([&](auto oc) { read_operand(oc); });
         L2A_FENCE();
-        static_for<0, 32>([&](auto mc) {
+        static_for<0, NS>([&](auto mc) {
             constexpr int mm = decltype(mc)::value;
             issue(mc);
-            if constexpr ((mm & 1) == 0) read_operand(Int<(mm >> 1) + kAhead>{});
-            static_for<0, 16>([&](auto qc) {
+            if constexpr (mm % NQB == 0) read_operand(Int<mm / NQB + kAhead>{});
+            static_for<0, 8 * NQB>([&](auto qc) {
                 constexpr int q = decltype(qc)::value;
                 if constexpr ((3 * q) / 2 == mm) exp_pair(qc);
             });
@@ -224,10 +237,10 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
             L2A_FENCE();
         });
 #pragma unroll
-        for (int c = 0; c < kNQB; ++c) l[c] += rsum[c];
-        // Both score buffers stay in AGPRs, where the matrix instructions write them; the VALU side
-        // fetches each element with acc_read where it is consumed.
-        asm volatile("" : "+a"(nxt.s[0]), "+a"(nxt.s[1]));
+        for (int c = 0; c < NQB; ++c) l[c] += rsum[c];
+        // With more than 256 registers both score buffers stay in AGPRs, where the matrix instructions
+        // write them; the VALU side fetches each element with acc_read where it is consumed.
+        if constexpr (NQB == 2) asm volatile("" : "+a"(nxt.s[0]), "+a"(nxt.s[1]));
     };
 
     // ---- prologue: K of the first two blocks, V of the first
@@ -243,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     // row sums stayed far from overflow and otherwise leaves the tile to the fix-up kernel.
     {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
 #pragma unroll
-        for (int c = 0; c < kNQB; ++c) mref[c] = -INFINITY;
+        for (int c = 0; c < NQB; ++c) mref[c] = -INFINITY;
         const int nb = jb0 < jb1 ? 2 : 1;
         for (int bi = 0; bi < nb; ++bi) {
 #pragma unroll
@@ -253,10 +266,10 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
                 for (int ks = 0; ks < 8; ++ks) {
                     const bf16x8 op = rm_operand(&lds_k[bi][0], kb * 32 + n, ks, h);
 #pragma unroll
-                    for (int c = 0; c < kNQB; ++c) S.s[c] = mfma32(op, qreg[c][ks], ks == 0 ? zero16 : S.s[c]);
+                    for (int c = 0; c < NQB; ++c) S.s[c] = mfma32(op, qreg[c][ks], ks == 0 ? zero16 : S.s[c]);
                 }
 #pragma unroll
-                for (int c = 0; c < kNQB; ++c)
+                for (int c = 0; c < NQB; ++c)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = (jb0 + bi) * kBK + kb * 32 + c_row(r, h);
@@ -265,7 +278,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
             }
         }
 #pragma unroll
-        for (int c = 0; c < kNQB; ++c) {
+        for (int c = 0; c < NQB; ++c) {
             mref[c] = fmaxf(mref[c], __shfl_xor(mref[c], 32)) * gm.scale_log2;
             if (!(mref[c] > -INFINITY)) mref[c] = 0.f;  // no key in reach yet: any finite reference will do
             negm[c] = -mref[c];
@@ -275,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
         for (int ks = 0; ks < 8; ++ks) {
             const bf16x8 op = rm_operand(&lds_k[0][0], n, ks, h);
 #pragma unroll
-            for (int c = 0; c < kNQB; ++c) Sa.s[c] = mfma32(op, qreg[c][ks], ks == 0 ? zero16 : Sa.s[c]);
+            for (int c = 0; c < NQB; ++c) Sa.s[c] = mfma32(op, qreg[c][ks], ks == 0 ? zero16 : Sa.s[c]);
         }
     }
 
@@ -301,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
                         L.vdst = lds_v0 + ((rel + 1) & 1) * (kD * kBK * 2);
                         L.krows = min(kBK, gm.T - jk * kBK);
                     }
-                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 8) issue_block_load(L, Int<mm - kLoadSlot0>{});
+                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 2 * NL) issue_block_load(L, Int<mm - kLoadSlot0>{});
                 });
                 half_block(mask_tag, Int<1>{}, Sb, Sa, &lds_k[kbuf1][0], 0, vt, jb * kBK + 32, [](auto) {});
             }
@@ -322,10 +335,10 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     }
 
     // ---- did every row sum stay in range?  (workgroup-wide vote; LDS is free after the last barrier)
-    float lt[kNQB];
+    float lt[NQB];
     bool bad = false;
 #pragma unroll
-    for (int c = 0; c < kNQB; ++c) {
+    for (int c = 0; c < NQB; ++c) {
         lt[c] = l[c] + __shfl_xor(l[c], 32);
         bad = bad || (wave_active && valid[c] && !(lt[c] > 0.f && lt[c] < 1.0e30f));
     }
@@ -345,7 +358,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs a) {
     __bf16* co = (__bf16*)a.out.copy_out;
     __bf16* zf = (__bf16*)a.out.zero_fill;
 #pragma unroll
-    for (int c = 0; c < kNQB; ++c) {
+    for (int c = 0; c < NQB; ++c) {
         if (!valid[c]) continue;
         const float inv = 1.f / lt[c];
         const size_t base = (((size_t)b * gm.T + pos[c]) * gm.Hq + head[c]) * kD + 4 * h;
@@ -616,9 +629,9 @@ int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, cons
     {
         KernelTimer kt(rs.local ? "fwd_local" : "fwd_global", st);
         if (rs.local)
-            hipLaunchKernelGGL((fwd_kernel<true>), grid, dim3(kThreads), 0, st, a);
+            hipLaunchKernelGGL((fwd_kernel<true, kFwdNQB, kFwdNW>), grid, dim3(64 * kFwdNW), 0, st, a);
         else
-            hipLaunchKernelGGL((fwd_kernel<false>), grid, dim3(kThreads), 0, st, a);
+            hipLaunchKernelGGL((fwd_kernel<false, kFwdNQB, kFwdNW>), grid, dim3(64 * kFwdNW), 0, st, a);
     }
     {
         KernelTimer kt(rs.local ? "fwd_local_fixup" : "fwd_global_fixup", st);
