@@ -8,36 +8,55 @@ constexpr int kThreads = 256;
 
 // delta_l[b,h,t] = <dO, S>, delta_g[b,h,t] = <dO, A>  (the "D" vector of the FlashAttention
 // backward, one per branch; delta_g is also the task-loss part of the router-score gradient,
-// Sec. 3.3 Eq. 7).  Sixteen lanes share one (b, t, h) row.
+// Sec. 3.3 Eq. 7).  A workgroup takes `tok` consecutive tokens of one sequence -- a contiguous
+// stretch of [t, h, D] rows, sixteen lanes per row -- and transposes its results through LDS, so
+// that the [b, h, t] outputs are written in runs of consecutive t instead of one scattered float
+// per row.
 template <typename E, int DL>
 __global__ __launch_bounds__(kThreads) void row_deltas_kernel(Geom gm, const E* __restrict__ dO,
                                                               const E* __restrict__ S, const E* __restrict__ A,
                                                               float* __restrict__ delta_l,
-                                                              float* __restrict__ delta_g) {
-    const long long row = (long long)blockIdx.x * (kThreads / 16) + (threadIdx.x >> 4);
+                                                              float* __restrict__ delta_g, int tok) {
+    extern __shared__ float stage[];  // [2][Hq][tok]
+    const int b = blockIdx.y, t0 = blockIdx.x * tok;
+    const int ntok = min(tok, gm.T - t0);
     const int part = threadIdx.x & 15;
-    const long long nrows = (long long)gm.B * gm.T * gm.Hq;
-    if (row >= nrows) return;
-    const size_t off = (size_t)row * gm.D + part * DL;
-    float a = 0.f, c = 0.f;
+    float* sa = stage;
+    float* sc = stage + gm.Hq * tok;
+    const size_t row0 = ((size_t)b * gm.T + t0) * gm.Hq;
+    for (int r = threadIdx.x >> 4; r < ntok * gm.Hq; r += kThreads / 16) {
+        const size_t off = (row0 + r) * gm.D + part * DL;
+        float a = 0.f, c = 0.f;
+        // one 16- or 32-byte load per array and lane
+        typedef E Vec __attribute__((ext_vector_type(DL)));
+        const Vec gv = *reinterpret_cast<const Vec*>(dO + off);
+        if (S) {
+            const Vec sv = *reinterpret_cast<const Vec*>(S + off);
 #pragma unroll
-    for (int i = 0; i < DL; ++i) {
-        const float g = (float)dO[off + i];
-        if (S) a += g * (float)S[off + i];
-        if (A) c += g * (float)A[off + i];
+            for (int i = 0; i < DL; ++i) a += (float)gv[i] * (float)sv[i];
+        }
+        if (A) {
+            const Vec av = *reinterpret_cast<const Vec*>(A + off);
+#pragma unroll
+            for (int i = 0; i < DL; ++i) c += (float)gv[i] * (float)av[i];
+        }
+        for (int o = 8; o > 0; o >>= 1) {
+            a += __shfl_xor(a, o);
+            c += __shfl_xor(c, o);
+        }
+        if (part == 0) {
+            const int tt = r / gm.Hq, h = r - tt * gm.Hq;
+            sa[h * tok + tt] = a;
+            sc[h * tok + tt] = c;
+        }
     }
-    for (int o = 8; o > 0; o >>= 1) {
-        a += __shfl_xor(a, o);
-        c += __shfl_xor(c, o);
-    }
-    if (part == 0) {
-        const int h = (int)(row % gm.Hq);
-        const long long bt = row / gm.Hq;
-        const int t = (int)(bt % gm.T);
-        const int b = (int)(bt / gm.T);
-        const size_t so = ((size_t)b * gm.Hq + h) * gm.T + t;
-        if (delta_l) delta_l[so] = a;
-        if (delta_g) delta_g[so] = c;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < gm.Hq * tok; idx += kThreads) {
+        const int h = idx / tok, tt = idx - h * tok;
+        if (tt >= ntok) continue;
+        const size_t so = ((size_t)b * gm.Hq + h) * gm.T + t0 + tt;
+        if (delta_l) delta_l[so] = sa[idx];
+        if (delta_g) delta_g[so] = sc[idx];
     }
 }
 
@@ -51,17 +70,20 @@ __global__ __launch_bounds__(kThreads) void fill_u32_kernel(uint32_t* p, size_t 
 
 int row_deltas(const Geom& g, int dtype, const void* dO, const void* S, const void* A, float* delta_l,
                float* delta_g, hipStream_t st) {
-    const long long nrows = (long long)g.B * g.T * g.Hq;
-    const dim3 grid((unsigned)((nrows + kThreads / 16 - 1) / (kThreads / 16)));
+    int tok = 64;  // tokens per workgroup: as many as fit 64 KB of LDS with Hq heads
+    while (tok > 1 && sizeof(float) * 2 * g.Hq * tok > 64 * 1024) tok /= 2;
+    const size_t lds = sizeof(float) * 2 * g.Hq * tok;
+    if (lds > 64 * 1024) return L2A_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)((g.T + tok - 1) / tok), (unsigned)g.B);
     KernelTimer kt("row_deltas", st);
     if (dtype == L2A_FP32 && g.D == 64)
-        hipLaunchKernelGGL((row_deltas_kernel<float, 4>), grid, dim3(kThreads), 0, st, g, (const float*)dO, (const float*)S, (const float*)A, delta_l, delta_g);
+        hipLaunchKernelGGL((row_deltas_kernel<float, 4>), grid, dim3(kThreads), lds, st, g, (const float*)dO, (const float*)S, (const float*)A, delta_l, delta_g, tok);
     else if (dtype == L2A_FP32 && g.D == 128)
-        hipLaunchKernelGGL((row_deltas_kernel<float, 8>), grid, dim3(kThreads), 0, st, g, (const float*)dO, (const float*)S, (const float*)A, delta_l, delta_g);
+        hipLaunchKernelGGL((row_deltas_kernel<float, 8>), grid, dim3(kThreads), lds, st, g, (const float*)dO, (const float*)S, (const float*)A, delta_l, delta_g, tok);
     else if (dtype == L2A_BF16 && g.D == 64)
-        hipLaunchKernelGGL((row_deltas_kernel<__bf16, 4>), grid, dim3(kThreads), 0, st, g, (const __bf16*)dO, (const __bf16*)S, (const __bf16*)A, delta_l, delta_g);
+        hipLaunchKernelGGL((row_deltas_kernel<__bf16, 4>), grid, dim3(kThreads), lds, st, g, (const __bf16*)dO, (const __bf16*)S, (const __bf16*)A, delta_l, delta_g, tok);
     else if (dtype == L2A_BF16 && g.D == 128)
-        hipLaunchKernelGGL((row_deltas_kernel<__bf16, 8>), grid, dim3(kThreads), 0, st, g, (const __bf16*)dO, (const __bf16*)S, (const __bf16*)A, delta_l, delta_g);
+        hipLaunchKernelGGL((row_deltas_kernel<__bf16, 8>), grid, dim3(kThreads), lds, st, g, (const __bf16*)dO, (const __bf16*)S, (const __bf16*)A, delta_l, delta_g, tok);
     else
         return L2A_ERR_UNSUPPORTED;
     return launch_status();
