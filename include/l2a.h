@@ -79,7 +79,8 @@ const char* l2a_strerror(int code);
  * calls; calls that share one workspace must be ordered on one stream.  What it holds:
  *   route     one int32 count per (b, mask head, 2048-position chunk)
  *   forward   bf16, D = 128 without L2A_FLAG_SCALAR: a token-minor copy [B,Hkv,D,ceil64(T)] of
- *             each branch's V and one int32 flag per tile of 256 rows; else nothing
+ *             each branch's V and one int32 flag per tile of 256 rows (tiles per (b, KV head)
+ *             rounded up to a multiple of 8); else nothing
  *   backward  delta_t of each branch, [B,Hq,T] float, twice; on the matrix-core path also a
  *             token-minor copy of each branch's K and, per branch, compact copies of the rows'
  *             Q and dO (row-major and token-minor, ceil64(T G) rows per (b, KV head)) with

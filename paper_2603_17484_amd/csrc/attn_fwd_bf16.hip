@@ -76,8 +76,19 @@ __global__ __launch_bounds__(64 * NW) void fwd_kernel(FwdArgs a) {
     const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
     const int n_rows = rows_total(a.rs, gm, bh);
     const int n_tiles = (n_rows + kBQ - 1) / kBQ;
-    if ((int)blockIdx.x >= n_tiles) return;
-    const int tile = n_tiles - 1 - (int)blockIdx.x;  // longest prefixes first
+    // Workgroups are dealt round-robin to the 8 XCDs (the grid's width is a multiple of 8).  Global
+    // rows: longest prefixes first; every tile starts at key block 0, so the tiles resident on an XCD
+    // read the same K/V block at about the same time whatever their order.  Local rows: each XCD
+    // takes a contiguous range of tiles, so that the tiles resident on it have overlapping windows
+    // and share their K/V blocks through its L2.
+    int tile;
+    if (LOCAL) {
+        const int per = (int)gridDim.x >> 3;
+        tile = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+    } else {
+        tile = n_tiles - 1 - (int)blockIdx.x;
+    }
+    if (tile < 0 || tile >= n_tiles) return;
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -623,7 +634,7 @@ int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, cons
     if ((unsigned long long)vt_cap * 2ull * kD > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
     FwdArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)vt, vt_cap, redo, out};
     const long long rows = (long long)g.T * g.G;
-    const dim3 grid((unsigned)((rows + kBQ - 1) / kBQ), g.B * g.Hkv);
+    const dim3 grid((unsigned)(((rows + kBQ - 1) / kBQ + 7) / 8 * 8), g.B * g.Hkv);  // a multiple of 8: see the tile order
     int r = fill_zero(redo, sizeof(int32_t) * grid.x * grid.y, st);
     if (r != L2A_OK) return r;
     {
@@ -646,7 +657,7 @@ int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, cons
 // number of redo flags mfma_fwd needs
 size_t mfma_fwd_redo_entries(const Geom& g) {
     const long long rows = (long long)g.T * g.G;
-    return (size_t)((rows + kBQ - 1) / kBQ) * g.B * g.Hkv;
+    return (size_t)(((rows + kBQ - 1) / kBQ + 7) / 8 * 8) * g.B * g.Hkv;
 }
 
 }  // namespace l2a

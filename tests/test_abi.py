@@ -45,7 +45,7 @@ def test_workspace_queries(lib):
     Bn, T, Hq, Hkv, D, G = 1, 131072, 28, 4, 128, 7
     up = lambda x, m: (x + m - 1) // m * m
     kv_copy = Bn * Hkv * D * up(T, 64) * 2            # token-minor copy of K or V, bf16
-    redo = up(4 * up(T * G, 256) // 256 * Bn * Hkv, 256)
+    redo = up(4 * up(up(T * G, 256) // 256, 8) * Bn * Hkv, 256)   # tiles per (b, KV head): a multiple of 8
     delta = up(4 * Bn * Hq * T, 256)
     cap = up(T * G, 64)
     packed = 4 * (Bn * Hkv * cap * D * 2) + 3 * up(Bn * Hkv * cap * 4, 256)
