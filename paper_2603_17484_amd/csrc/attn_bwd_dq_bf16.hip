@@ -21,9 +21,7 @@ namespace {
 
 constexpr int kBK = 64;
 constexpr int kRW = 32;        // rows per wavefront
-constexpr int kBQ = 4 * kRW;   // rows per workgroup
 constexpr int kAhead = 3;      // operand look-ahead, in slots
-constexpr int kLoadSlot0 = 12;  // the loads of later blocks go out in slots 12-23 of a block's first half
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -49,8 +47,16 @@ struct SdP {
     f32x16 s, dp;  // 32 keys x 32 rows each
 };
 
-template <bool LOCAL>
-__global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
+// NW wavefronts of 32 rows per workgroup.  With 8 the register budget is 256 per wavefront and two
+// share a SIMD: the loop over unmasked blocks fits without spills and gains 14 %, the masked blocks
+// spill -- so the Global rows (a handful of masked blocks out of hundreds per tile) run with 8
+// wavefronts and the Local rows (every twentieth block masked) with 4.
+template <bool LOCAL, int NW>
+__global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
+    constexpr int kNW = NW;
+    constexpr int kBQ = NW * kRW;            // rows per workgroup
+    constexpr int kNL = 16 / NW;             // 16-byte loads a wavefront issues per K, V or K^T block
+    constexpr int kLoadSlot0 = 23 - 3 * kNL;  // the loads of later blocks go out in the last slots of a block's first half
     __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
     __shared__ __attribute__((aligned(1024))) __bf16 lds_v[3][kBK * 128];
     __shared__ __attribute__((aligned(1024))) __bf16 lds_kt[2][kD * kBK];
@@ -122,8 +128,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     const char* ktbase = (const char*)(a.kt + (size_t)bh * kD * a.kt_cap);
     const unsigned lds_k0 = lds_offset(&lds_k[0][0]), lds_v0 = lds_offset(&lds_v[0][0]);
     const unsigned lds_kt0 = lds_offset(&lds_kt[0][0]);
-    const RmDma<kBK> kv_off = rm_dma_setup<kBK>(kv_row_bytes, wave);
-    const TmDma<kBK> kt_off = tm_dma_setup<kBK>((unsigned)a.kt_cap * 2u, wave);
+    const RmDma<kBK, kNW> kv_off = rm_dma_setup<kBK, kNW>(kv_row_bytes, wave);
+    const TmDma<kBK, kNW> kt_off = tm_dma_setup<kBK, kNW>((unsigned)a.kt_cap * 2u, wave);
     auto load_kv = [&](int jb, int buf) __attribute__((always_inline)) {
         const size_t src = (size_t)jb * kBK * kv_row_bytes;
         const unsigned dk_ = lds_k0 + buf * (kBK * 256), dv_ = lds_v0 + buf * (kBK * 256);
@@ -131,8 +137,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
             rm_dma_issue(kv_off, kbase + src, dk_, wave);
             rm_dma_issue(kv_off, vbase + src, dv_, wave);
         } else {  // keys past the end of the sequence are clamped: always masked, never out of bounds
-            rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, kbase + src, dk_, wave);
-            rm_dma_issue_clamped<kBK>(kv_row_bytes, gm.T - jb * kBK, vbase + src, dv_, wave);
+            rm_dma_issue_clamped<kBK, kNW>(kv_row_bytes, gm.T - jb * kBK, kbase + src, dk_, wave);
+            rm_dma_issue_clamped<kBK, kNW>(kv_row_bytes, gm.T - jb * kBK, vbase + src, dv_, wave);
         }
     };
     auto load_kt = [&](int jb, int buf) __attribute__((always_inline)) {
@@ -153,13 +159,14 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
     };
     auto issue_block_load = [&](const BlockLoads& L, auto ic) __attribute__((always_inline)) {
         constexpr int i = decltype(ic)::value;
-        if constexpr (i < 8) {
-            const unsigned row = (unsigned)min(k_lane_row + 16 * (i & 3), L.krows - 1);
+        if constexpr (i < 2 * kNL) {
+            constexpr int j = i % kNL;
+            const unsigned row = (unsigned)min(k_lane_row + 4 * kNW * j, L.krows - 1);
             const unsigned voff = __umul24(row, kv_row_bytes) + k_lane_chunk;
-            if constexpr (i < 4) dma16_so(L.ksrc, voff, L.kdst + (i * 4 + wave) * 1024);
-            else dma16_so(L.vsrc, voff, L.vdst + ((i - 4) * 4 + wave) * 1024);
+            if constexpr (i < kNL) dma16_so(L.ksrc, voff, L.kdst + (j * kNW + wave) * 1024);
+            else dma16_so(L.vsrc, voff, L.vdst + (j * kNW + wave) * 1024);
         } else {
-            dma16_so(L.ktsrc, kt_off.voff[i - 8], L.ktdst + ((i - 8) * 4 + wave) * 1024);
+            dma16_so(L.ktsrc, kt_off.voff[i - 2 * kNL], L.ktdst + ((i - 2 * kNL) * kNW + wave) * 1024);
         }
     };
 
@@ -291,7 +298,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(DqArgs a) {
                         L.ktdst = lds_kt0 + ((rel + 1) & 1) * (kD * kBK * 2);
                         L.krows = min(kBK, gm.T - jk * kBK);
                     }
-                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 12) issue_block_load(L, Int<mm - kLoadSlot0>{});
+                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 3 * kNL) issue_block_load(L, Int<mm - kLoadSlot0>{});
                 });
                 half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], &lds_v[buf1][0], 0, ktt, jb * kBK + 32,
                            [](auto) {});
@@ -342,12 +349,14 @@ int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, c
     DqArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)kt, kt_cap,
              (const __bf16*)dO, lse, delta, (__bf16*)dq, accumulate};
     const long long rows = (long long)g.T * g.G;
-    const dim3 grid((unsigned)(((rows + kBQ - 1) / kBQ + 7) / 8 * 8), g.B * g.Hkv);  // a multiple of 8: see the tile order
+    constexpr int kNwLocal = 4, kNwGlobal = 8;
+    const int bq = (rs.local ? kNwLocal : kNwGlobal) * kRW;
+    const dim3 grid((unsigned)(((rows + bq - 1) / bq + 7) / 8 * 8), g.B * g.Hkv);  // a multiple of 8: see the tile order
     KernelTimer kt_(rs.local ? "bwd_dq_local" : "bwd_dq_global", st);
     if (rs.local)
-        hipLaunchKernelGGL((bwd_dq_kernel<true>), grid, dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((bwd_dq_kernel<true, kNwLocal>), grid, dim3(64 * kNwLocal), 0, st, a);
     else
-        hipLaunchKernelGGL((bwd_dq_kernel<false>), grid, dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL((bwd_dq_kernel<false, kNwGlobal>), grid, dim3(64 * kNwGlobal), 0, st, a);
     return launch_status();
 }
 
