@@ -6,14 +6,18 @@
 // Global rows from kblk_first_row on.  The G heads of a KV group are rows of the same list, so
 // the sum over the heads of a group needs no second pass.
 //
-// Rows are read from the compact copies the pack pre-pass makes of each branch's Q and dO
-// (row-major for S = Q K^T and dP = dO V^T, token-minor for dV += P^T dO and dK += dS^T Q)
-// together with the rows' log-sum-exp, -delta and position, by direct global->LDS loads.  The dP
-// accumulators start from -delta, so that dS = P o dP' needs no subtraction.
-//   S  [row, key] = Q K^T     A = Q tile (LDS, row-major),  B = K (registers, loaded once)
+// Rows are read from the compact row-major copies the pack pre-pass makes of each branch's Q and
+// dO, together with the rows' log-sum-exp, -delta and position, by direct global->LDS loads.  One
+// tile in LDS serves both orientations: S = Q K^T and dP = dO V^T read its rows, dV += P^T dO and
+// dK += dS^T Q read it transposed (ds_read_b64_tr_b16; the tile's chunk permutation keeps both
+// kinds of read free of bank conflicts).  The load path into LDS is the scarcer resource (64 B/clk
+// per CU against 188 B/clk of LDS reads), so loading a second, token-minor copy of every tile
+// costs more than the half-rate transposed reads do.  The dP accumulators start from -delta, so
+// that dS = P o dP' needs no subtraction.
+//   S  [row, key] = Q K^T     A = Q tile (LDS, rows),        B = K (registers, loaded once)
 //   dP [row, key] = dO V^T    A = dO tile,                   B = V (registers)
-//   dV [key, ch] += P^T dO    A = P^T  = the S accumulators,  B = dO tile (LDS, token-minor)
-//   dK [key, ch] += dS^T Q    A = dS^T = the dP accumulators, B = Q tile (LDS, token-minor)
+//   dV [key, ch] += P^T dO    A = P^T  = the S accumulators,  B = dO tile (LDS, transposed reads)
+//   dK [key, ch] += dS^T Q    A = dS^T = the dP accumulators, B = Q tile (LDS, transposed reads)
 // Software pipeline per tile (32 matrix-core instructions = 32 slots): S, dP of the next tile
 // (slots 0-15) and the dV, dK update of this tile (slots 16-31) run on the matrix cores while the
 // VALU turns this tile's S, dP into P and dS.
@@ -25,10 +29,10 @@ namespace {
 constexpr int kKeysPerWg = 128;
 constexpr int kRT = 32;     // rows per tile
 constexpr int kAhead = 3;   // operand look-ahead, in slots
-constexpr int kNB = 4;              // LDS buffers per tile kind: loads run kNB - 1 tiles ahead
-constexpr int kDmaPerStep = 11;     // direct-to-LDS instructions a wavefront issues per tile step
+constexpr int kNB = 8;              // LDS buffers: loads run kNB - 1 tiles ahead
+constexpr int kDmaPerStep = 7;      // direct-to-LDS instructions a wavefront issues per tile step
 constexpr int kLoadSlot0 = 1;       // ... in slots kLoadSlot0 + kLoadStride i of a step, i = 0 .. 10: the four wavefronts
-constexpr int kLoadStride = 3;      // issue theirs at about the same time, and the load path takes them one by one
+constexpr int kLoadStride = 4;      // issue theirs at about the same time, and the load path takes them one by one
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -62,14 +66,10 @@ struct DkdvArgs {
 struct RowTileLds {
     __bf16 q_rm[kRT * 128];
     __bf16 g_rm[kRT * 128];
-    float ndelta[64];  // 32 used; a whole wavefront writes 64 entries
-};
-struct ColTileLds {
-    __bf16 q_t[kD * kRT];
-    __bf16 g_t[kD * kRT];
+    float ndelta[64];  // per-row statistics: 32 used; a whole wavefront writes 64 entries
     float lse2[64];
     int pos[64];
-    int pad[128];
+    int pad[64];
 };
 
 struct SdP {
@@ -78,7 +78,6 @@ struct SdP {
 
 __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     __shared__ __attribute__((aligned(1024))) RowTileLds lds_rm[kNB];
-    __shared__ __attribute__((aligned(1024))) ColTileLds lds_tm[kNB];
 
     const Geom& gm = a.gm;
     const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
@@ -154,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     const int total = n0 + n1;
 
     // ---- loads.  Flat tile index it -> (set, tile)
-    const unsigned lds_rm0 = lds_offset(&lds_rm[0]), lds_tm0 = lds_offset(&lds_tm[0]);
+    const unsigned lds_rm0 = lds_offset(&lds_rm[0]);
     // A Global set is walked downwards from its last tile, so that all key blocks of a head read the
     // same tile at the same step (they only stop at different tiles).  A Local set is walked upwards,
     // but every key block of an XCD's chunk starts at the first tile of the chunk's *last* key block
@@ -205,15 +204,14 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         c.i = more ? c.i + 1 : c.i;
     };
     // Every load is a wave-uniform base plus a per-lane offset fixed for the whole kernel.
-    const RmDma<kRT> rm_off = rm_dma_setup<kRT>(kD * 2, wave);
-    const TmDma<kRT> tm_off = tm_dma_setup<kRT>((unsigned)a.cap * 2u, wave);
+    const RmDma<kRT> rm_off = rm_tr_dma_setup<kRT>(kD * 2, wave);
     const unsigned stat_off = n * 4;
     const size_t rows_bh = (size_t)bh * a.cap;
-    // The 11 loads of a step (5 for a row-major tile, 6 for a token-minor tile), numbered so that the
-    // tile steps can issue them one at a time between matrix instructions.
+    // The 7 loads of a step (the Q and dO rows of a tile, row-major, and three per-row statistics),
+    // numbered so that the tile steps can issue them one at a time between matrix instructions.
     struct StepLoads {
-        size_t rm256, rm4, tm2, tm4;  // byte offsets of the tiles inside the packed arrays
-        unsigned dst_rm, dst_tm;      // LDS buffers
+        size_t rm256, rm4;  // byte offsets of the tile inside the packed arrays
+        unsigned dst_rm;    // LDS buffer
     };
     auto stage_rm = [&](StepLoads& L, long long cset, int ct, int buf) __attribute__((always_inline)) {
         const size_t set = (size_t)cset, row0 = rows_bh + (size_t)ct * kRT;
@@ -221,30 +219,21 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         L.rm4 = set + row0 * 4;
         L.dst_rm = __builtin_amdgcn_readfirstlane(lds_rm0 + buf * (unsigned)sizeof(RowTileLds));
     };
-    auto stage_tm = [&](StepLoads& L, long long cset, int ct, int buf) __attribute__((always_inline)) {
-        const size_t set = (size_t)cset;
-        L.tm2 = set + (rows_bh * kD + (size_t)ct * kRT) * 2;
-        L.tm4 = set + (rows_bh + (size_t)ct * kRT) * 4;
-        L.dst_tm = __builtin_amdgcn_readfirstlane(lds_tm0 + buf * (unsigned)sizeof(ColTileLds));
-    };
     auto issue_load = [&](const StepLoads& L, auto kc) __attribute__((always_inline)) {
         constexpr int k = decltype(kc)::value;
-        if constexpr (k < 5) {
-            // per-row statistics (k = 4): 32 rows, the upper half-wave repeats the lower one (every
-            // wavefront issues them, identically, so that all have the same number of loads in flight)
-            if constexpr (k < 2) dma16_so(a.rows.qc + L.rm256, rm_off.voff[k], L.dst_rm + (k * 4 + wave) * 1024);
-            else if constexpr (k < 4)
-                dma16_so(a.rows.gc + L.rm256, rm_off.voff[k - 2], L.dst_rm + kRT * 256 + ((k - 2) * 4 + wave) * 1024);
-            else dma4_so(a.rows.ndelta + L.rm4, stat_off, L.dst_rm + 2 * kRT * 256);
-        } else {
-            if constexpr (k < 7) dma16_so(a.rows.qt + L.tm2, tm_off.voff[k - 5], L.dst_tm + ((k - 5) * 4 + wave) * 1024);
-            else if constexpr (k < 9)
-                dma16_so(a.rows.gt + L.tm2, tm_off.voff[k - 7], L.dst_tm + kD * kRT * 2 + ((k - 7) * 4 + wave) * 1024);
-            else if constexpr (k == 9) dma4_so(a.rows.lse2 + L.tm4, stat_off, L.dst_tm + 2 * kD * kRT * 2);
-            else dma4_so(a.rows.pos + L.tm4, stat_off, L.dst_tm + 2 * kD * kRT * 2 + 256);
-        }
+        // per-row statistics (k >= 4): 32 rows, the upper half-wave repeats the lower one (every
+        // wavefront issues them, identically, so that all have the same number of loads in flight)
+        if constexpr (k < 2) dma16_so(a.rows.qc + L.rm256, rm_off.voff[k], L.dst_rm + (k * 4 + wave) * 1024);
+        else if constexpr (k < 4)
+            dma16_so(a.rows.gc + L.rm256, rm_off.voff[k - 2], L.dst_rm + kRT * 256 + ((k - 2) * 4 + wave) * 1024);
+        else if constexpr (k == 4) dma4_so(a.rows.ndelta + L.rm4, stat_off, L.dst_rm + 2 * kRT * 256);
+        else if constexpr (k == 5) dma4_so(a.rows.lse2 + L.rm4, stat_off, L.dst_rm + 2 * kRT * 256 + 256);
+        else dma4_so(a.rows.pos + L.rm4, stat_off, L.dst_rm + 2 * kRT * 256 + 512);
     };
 
+    unsigned tr_off[4][2];  // this lane's part of the transposed reads' addresses
+#pragma unroll
+    for (int d = 0; d < 4; ++d) tr_off[d][0] = rm_tr_col_offset(d, 0, lane), tr_off[d][1] = rm_tr_col_offset(d, 1, lane);
     f32x16 dkacc[4], dvacc[4];
 #pragma unroll
     for (int d = 0; d < 4; ++d)
@@ -257,11 +246,17 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
 
     // One tile: P, dS from `cur` (tile it; statistics and token-minor tiles in ct) overlapped with
     // S, dP of tile it+1 into `nxt` (row-major tiles rt) and the dV, dK update of tile it.
-    auto tile_step = [&](auto mask_tag, SdP& cur, SdP& nxt, const RowTileLds& rt, const ColTileLds& ct, bool local,
+    auto tile_step = [&](auto mask_tag, SdP& cur, SdP& nxt, const RowTileLds& rt, const RowTileLds& ct, bool local,
                          auto&& stage_loads, auto&& loads_issued) __attribute__((always_inline)) {
         StepLoads L;
         constexpr bool MASK = decltype(mask_tag)::value;
         const float c2 = gm.scale_log2;
+        lds_cptr trp[4][2];  // this lane's pieces of the transposed reads in tile ct
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            trp[d][0] = (lds_cptr)(uintptr_t)(lds_offset(&ct) + tr_off[d][0]);
+            trp[d][1] = (lds_cptr)(uintptr_t)(lds_offset(&ct) + tr_off[d][1]);
+        }
         bf16x8 opnd[32 + kAhead];
         uint32_t pw[2][4], dsw[2][4];  // P^T, dS^T as packed bf16 pairs: [16-row group][dword]
         f32x4 l2[4];
@@ -279,12 +274,11 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         auto read_operand = [&](auto mc) {
             constexpr int mm = decltype(mc)::value;
             if constexpr (mm < 16) {
-                if constexpr ((mm & 1) == 0) opnd[mm] = rm_operand(rt.q_rm, n, mm >> 1, h);
-                else opnd[mm] = rm_operand(rt.g_rm, n, mm >> 1, h);
+                if constexpr ((mm & 1) == 0) opnd[mm] = rm_tr_row_operand(rt.q_rm, n, mm >> 1, h);
+                else opnd[mm] = rm_tr_row_operand(rt.g_rm, n, mm >> 1, h);
             } else if constexpr (mm < 32) {
                 constexpr int x = mm - 16, step = x >> 3, d = (x >> 1) & 3;
-                if constexpr ((x & 1) == 0) opnd[mm] = tm_operand<kRT>(ct.g_t, d * 32 + n, step, h);
-                else opnd[mm] = tm_operand<kRT>(ct.q_t, d * 32 + n, step, h);
+                opnd[mm] = rm_tr_col_operand_at(trp[d][0], trp[d][1], step, (x & 1) == 0 ? kRT * 256 : 0);  // dO / Q tile
             }
         };
         auto issue = [&](auto mc) {
@@ -351,21 +345,14 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     };
 
     if (total > 0) {
-        // ---- prologue: row-major tiles 0 and 1, token-minor tile 0; S, dP of tile 0
+        // ---- prologue: tiles 0 .. kNB-2; S, dP of tile 0
         SdP Xa, Xb;
-        // The token-minor loads run one tile behind the row-major ones: they use the cursor's last position.
         Cursor lc = cursor_begin();
-        long long tm_set = lc.set;
-        int tm_t = lc.t;
-        static_for<0, kNB>([&](auto ic) {
+        static_for<0, kNB - 1>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             StepLoads L;
             stage_rm(L, lc.set, lc.t, i);
-            stage_tm(L, lc.set, lc.t, i);
-            static_for<0, kDmaPerStep>([&](auto kc) {
-                if constexpr (decltype(kc)::value < 5 || i < kNB - 1) issue_load(L, kc);
-            });
-            tm_set = lc.set, tm_t = lc.t;
+            static_for<0, kDmaPerStep>([&](auto kc) { issue_load(L, kc); });
             advance(lc);
         });
         dma_wait();
@@ -374,30 +361,25 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         for (int e = 0; e < 16; ++e) Xa.dp[e] = lds_rm[0].ndelta[c_row(e, h)];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 qa = rm_operand(lds_rm[0].q_rm, n, ks, h), ga = rm_operand(lds_rm[0].g_rm, n, ks, h);
+            const bf16x8 qa = rm_tr_row_operand(lds_rm[0].q_rm, n, ks, h), ga = rm_tr_row_operand(lds_rm[0].g_rm, n, ks, h);
             if (ks == 0) mfma32_vgpr_first(Xa.s, qa, kreg[ks]);
             else mfma32_vgpr_acc(Xa.s, qa, kreg[ks]);
             mfma32_vgpr_acc(Xa.dp, ga, vreg[ks]);
         }
         mfma_vgpr_settle();  // the first tile step reads Xa at once
 
-        // Step `it` reads the row-major tile it+1 and the token-minor tile it, and in its second half
-        // issues the loads of row-major tile it+kNB (into the buffer tile `it` left one step ago) and
-        // token-minor tile it+kNB-1 (buffer of tile it-1).  At its end only the loads of the last
-        // kNB-2 steps may still be in flight.  Two tiles per trip so that the two S/dP buffers swap
-        // roles without copies.
+        // Step `it` reads the rows of tile it+1 and tile `it` transposed, and issues the loads of tile
+        // it+kNB-1 (into the buffer tile it-1 left one step ago).  At its end only the loads of the last
+        // kNB-3 steps may still be in flight: tile it+2 has landed.  Two tiles per trip so that the two
+        // S/dP buffers swap roles without copies.
         auto one = [&](auto mask_tag, SdP& cur, SdP& nxt, int it, bool local) __attribute__((always_inline)) {
             static_assert((kNB & (kNB - 1)) == 0, "buffer indices are taken with a mask");
-            tile_step(mask_tag, cur, nxt, lds_rm[(it + 1) & (kNB - 1)], lds_tm[it & (kNB - 1)], local,
+            tile_step(mask_tag, cur, nxt, lds_rm[(it + 1) & (kNB - 1)], lds_rm[it & (kNB - 1)], local,
                       [&](StepLoads& L) __attribute__((always_inline)) {
-                          stage_rm(L, lc.set, lc.t, it & (kNB - 1));
-                          stage_tm(L, tm_set, tm_t, (it + kNB - 1) & (kNB - 1));
+                          stage_rm(L, lc.set, lc.t, (it + kNB - 1) & (kNB - 1));
                       },
-                      [&]() __attribute__((always_inline)) {
-                          tm_set = lc.set, tm_t = lc.t;
-                          advance(lc);
-                      });
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kNB - 2) * kDmaPerStep) : "memory");
+                      [&]() __attribute__((always_inline)) { advance(lc); });
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kNB - 3) * kDmaPerStep) : "memory");
             __syncthreads();
         };
         // The two S/dP buffers swap roles every tile; which one holds the current tile is carried

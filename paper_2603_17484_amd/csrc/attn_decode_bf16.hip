@@ -28,8 +28,6 @@ constexpr int kWaves = 1;     // wavefronts per workgroup
 constexpr int kBufs = 1;     // LDS buffers per wavefront (1: two workgroups per CU overlap each other's loads)
 constexpr int kPart = kD + 4;  // floats per partial: max (log2 units), sum, 2 unused, O[128]
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 struct DecodeArgs {
     Geom gm;            // gm.T = capacity of the cache (tokens per sequence)
@@ -54,20 +52,6 @@ __device__ __forceinline__ bool head_routed(const DecodeArgs& a, int b, int head
     if (!a.mask) return true;
     const int mh = a.mask_heads == 1 ? 0 : (a.mask_heads == a.gm.Hq ? head : head / a.gm.G);
     return a.mask[(size_t)b * a.mask_heads + mh] != 0;
-}
-
-// A operand of O^T += V^T P^T from a row-major tile of 32 keys in the transposed-read swizzle: channel d*32+n, the
-// keys of 16-key group `step` in the order 4h..4h+3, 8+4h..8+4h+3 (the order P^T's rows come in).
-__device__ __forceinline__ bf16x8 v_transposed_operand(const __bf16* tile, int d, int step, int lane) {
-    const int i = lane & 15, n16 = (lane >> 4) & 1, h = lane >> 5;
-    const int ch = d * 32 + 16 * n16 + 4 * (i & 3);
-    const int row = 16 * step + 4 * h + (i >> 2);
-    auto addr = [&](int r) { return tile + r * 128 + (((ch >> 3) ^ rm_tr_swizzle(r)) * 8) + (ch & 7); };
-    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (s16x4 __attribute__((address_space(3)))*)(__attribute__((address_space(3))) const void*)addr(row));
-    const s16x4 v2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (s16x4 __attribute__((address_space(3)))*)(__attribute__((address_space(3))) const void*)addr(row + 8));
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v1, v2, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
 __global__ __launch_bounds__(64 * kWaves) void decode_partial_kernel(DecodeArgs a) {
@@ -191,7 +175,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_partial_kernel(DecodeArgs 
             const u32x4 pv = {pw[step][0], pw[step][1], pw[step][2], pw[step][3]};
 #pragma unroll
             for (int d = 0; d < 4; ++d)
-                oacc[d] = mfma32(v_transposed_operand(vt, d, step, lane), __builtin_bit_cast(bf16x8, pv), oacc[d]);
+                oacc[d] = mfma32(rm_tr_col_operand(vt, d, step, lane), __builtin_bit_cast(bf16x8, pv), oacc[d]);
         }
     }
     l += __shfl_xor(l, 32);

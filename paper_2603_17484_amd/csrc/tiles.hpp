@@ -100,6 +100,43 @@ __device__ __forceinline__ RmDma<ROWS, NW> rm_tr_dma_setup(unsigned row_stride_b
     }
     return d;
 }
+// Operands from a tile in that layout.  Row-major: row `row`, channels 16 ks + 8 h .. + 7.
+__device__ __forceinline__ bf16x8 rm_tr_row_operand(const __bf16* tile, int row, int ks, int h) {
+    const int slot = (2 * ks + h) ^ rm_tr_swizzle(row);
+    return *reinterpret_cast<const bf16x8*>(tile + row * 128 + slot * 8);
+}
+// Transposed (contraction over the rows): channel d*32 + (lane & 31), the rows of 16-row group `step`
+// in the order 4h..4h+3, 8+4h..8+4h+3 -- the order in which a C tile's registers hold them.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 rm_tr_col_operand(const __bf16* tile, int d, int step, int lane) {
+    const int i = lane & 15, n16 = (lane >> 4) & 1, h = lane >> 5;
+    const int ch = d * 32 + 16 * n16 + 4 * (i & 3);
+    const int row = 16 * step + 4 * h + (i >> 2);
+    auto addr = [&](int r) { return tile + r * 128 + (((ch >> 3) ^ rm_tr_swizzle(r)) * 8) + (ch & 7); };
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(__attribute__((address_space(3))) const void*)addr(row));
+    const s16x4 v2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(__attribute__((address_space(3))) const void*)addr(row + 8));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v1, v2, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+// The same read with the per-lane part of the address computed once: byte offset of this lane's piece for
+// channel block d and half j (rows 4h.., 8+4h..) of 16-row group 0; group `step` lies 4096 bytes further.
+__device__ __forceinline__ unsigned rm_tr_col_offset(int d, int j, int lane) {
+    const int i = lane & 15, n16 = (lane >> 4) & 1, h = lane >> 5;
+    const int ch = d * 32 + 16 * n16 + 4 * (i & 3);
+    const int r = 4 * h + (i >> 2) + 8 * j;
+    return (unsigned)(r * 256 + (((ch >> 3) ^ rm_tr_swizzle(r)) * 16) + (ch & 7) * 2);
+}
+// p0, p1: LDS addresses of this lane's two pieces in 16-row group 0 of the first of several tiles that lie
+// `tile_bytes` apart (tile address + rm_tr_col_offset(d, 0 / 1, lane)); the constant parts of the address
+// end up in the instruction's offset field.
+typedef __attribute__((address_space(3))) const char* lds_cptr;
+__device__ __forceinline__ bf16x8 rm_tr_col_operand_at(lds_cptr p0, lds_cptr p1, int step, int tile_bytes_off) {
+    typedef s16x4 __attribute__((address_space(3)))* lds_ptr;
+    const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + step * 4096 + tile_bytes_off));
+    const s16x4 v2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1 + step * 4096 + tile_bytes_off));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(v1, v2, 0, 1, 2, 3, 4, 5, 6, 7));
+}
 // sbase: global address of (row 0, channel 0) of the tile, wave-uniform
 template <int ROWS, int NW>
 __device__ __forceinline__ void rm_dma_issue(const RmDma<ROWS, NW>& d, const void* sbase, unsigned lds_base,
