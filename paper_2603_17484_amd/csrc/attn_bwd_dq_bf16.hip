@@ -56,10 +56,9 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     constexpr int kNW = NW;
     constexpr int kBQ = NW * kRW;            // rows per workgroup
     constexpr int kNL = 16 / NW;             // 16-byte loads a wavefront issues per K, V or K^T block
-    constexpr int kLoadSlot0 = 23 - 3 * kNL;  // the loads of later blocks go out in the last slots of a block's first half
+    constexpr int kLoadSlot0 = 23 - 2 * kNL;  // the loads of later blocks go out in the last slots of a block's first half
     __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
     __shared__ __attribute__((aligned(1024))) __bf16 lds_v[3][kBK * 128];
-    __shared__ __attribute__((aligned(1024))) __bf16 lds_kt[2][kD * kBK];
 
     const Geom& gm = a.gm;
     const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
@@ -125,11 +124,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     const size_t kv_head = ((size_t)b * gm.T * gm.Hkv + hk) * kD;
     const char* kbase = (const char*)(a.k + kv_head);
     const char* vbase = (const char*)(a.v + kv_head);
-    const char* ktbase = (const char*)(a.kt + (size_t)bh * kD * a.kt_cap);
     const unsigned lds_k0 = lds_offset(&lds_k[0][0]), lds_v0 = lds_offset(&lds_v[0][0]);
-    const unsigned lds_kt0 = lds_offset(&lds_kt[0][0]);
-    const RmDma<kBK, kNW> kv_off = rm_dma_setup<kBK, kNW>(kv_row_bytes, wave);
-    const TmDma<kBK, kNW> kt_off = tm_dma_setup<kBK, kNW>((unsigned)a.kt_cap * 2u, wave);
+    const RmDma<kBK, kNW> kv_off = rm_tr_dma_setup<kBK, kNW>(kv_row_bytes, wave);
     auto load_kv = [&](int jb, int buf) __attribute__((always_inline)) {
         const size_t src = (size_t)jb * kBK * kv_row_bytes;
         const unsigned dk_ = lds_k0 + buf * (kBK * 256), dv_ = lds_v0 + buf * (kBK * 256);
@@ -137,37 +133,33 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
             rm_dma_issue(kv_off, kbase + src, dk_, wave);
             rm_dma_issue(kv_off, vbase + src, dv_, wave);
         } else {  // keys past the end of the sequence are clamped: always masked, never out of bounds
-            rm_dma_issue_clamped<kBK, kNW>(kv_row_bytes, gm.T - jb * kBK, kbase + src, dk_, wave);
-            rm_dma_issue_clamped<kBK, kNW>(kv_row_bytes, gm.T - jb * kBK, vbase + src, dv_, wave);
+            rm_dma_issue_clamped<kBK, kNW, true>(kv_row_bytes, gm.T - jb * kBK, kbase + src, dk_, wave);
+            rm_dma_issue_clamped<kBK, kNW, true>(kv_row_bytes, gm.T - jb * kBK, vbase + src, dv_, wave);
         }
     };
-    auto load_kt = [&](int jb, int buf) __attribute__((always_inline)) {
-        tm_dma_issue(kt_off, ktbase + (size_t)jb * kBK * 2, lds_kt0 + buf * (kD * kBK * 2), wave);
-    };
-    // In the main loop the twelve loads of a block are issued one at a time between matrix
-    // instructions.  K and V rows are clamped to the end of the sequence on the fly (rows past it are
-    // always masked), so that the ragged last block needs no code path of its own:
-    // lane l of load i fetches chunk (l & 15) ^ (row & 15) of row (4 i + wave) * 4 + (l >> 4).
+    // In the main loop the loads of a block are issued one at a time between matrix instructions.
+    // K and V rows are clamped to the end of the sequence on the fly (rows past it are always masked),
+    // so that the ragged last block needs no code path of its own: lane l of load j fetches chunk
+    // (l & 15) ^ rm_tr_swizzle(row) of row (NW j + wave) * 4 + (l >> 4); the permutation depends on
+    // row & 15 only, which j does not change.
     const int k_lane_row = wave * 4 + (lane >> 4);
-    const unsigned k_lane_chunk = (unsigned)(((lane & 15) ^ (k_lane_row & 15)) * 16);
+    const unsigned k_lane_chunk = (unsigned)(((lane & 15) ^ rm_tr_swizzle(k_lane_row)) * 16);
     struct BlockLoads {
         const char* ksrc;
         const char* vsrc;
-        const char* ktsrc;
-        unsigned kdst, vdst, ktdst;
+        unsigned kdst, vdst;
         int krows;  // rows of the K, V block that exist
     };
+    unsigned tr_off[4][2];  // this lane's part of the transposed reads' addresses
+#pragma unroll
+    for (int d = 0; d < 4; ++d) tr_off[d][0] = rm_tr_col_offset(d, 0, lane), tr_off[d][1] = rm_tr_col_offset(d, 1, lane);
     auto issue_block_load = [&](const BlockLoads& L, auto ic) __attribute__((always_inline)) {
         constexpr int i = decltype(ic)::value;
-        if constexpr (i < 2 * kNL) {
-            constexpr int j = i % kNL;
-            const unsigned row = (unsigned)min(k_lane_row + 4 * kNW * j, L.krows - 1);
-            const unsigned voff = __umul24(row, kv_row_bytes) + k_lane_chunk;
-            if constexpr (i < kNL) dma16_so(L.ksrc, voff, L.kdst + (j * kNW + wave) * 1024);
-            else dma16_so(L.vsrc, voff, L.vdst + (j * kNW + wave) * 1024);
-        } else {
-            dma16_so(L.ktsrc, kt_off.voff[i - 2 * kNL], L.ktdst + ((i - 2 * kNL) * kNW + wave) * 1024);
-        }
+        constexpr int j = i % kNL;
+        const unsigned row = (unsigned)min(k_lane_row + 4 * kNW * j, L.krows - 1);
+        const unsigned voff = __umul24(row, kv_row_bytes) + k_lane_chunk;
+        if constexpr (i < kNL) dma16_so(L.ksrc, voff, L.kdst + (j * kNW + wave) * 1024);
+        else dma16_so(L.vsrc, voff, L.vdst + (j * kNW + wave) * 1024);
     };
 
     f32x16 acc[4];
@@ -187,15 +179,22 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
         bf16x8 opnd[24 + kAhead];
         uint32_t dsw[2][4];  // dS as packed bf16 pairs: [16-key group][dword]
         float dsum = 0.f;
+        lds_cptr trp[4][2];  // this lane's pieces of the transposed reads in tile ktt
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            trp[d][0] = (lds_cptr)(uintptr_t)(lds_offset(ktt) + tr_off[d][0]);
+            trp[d][1] = (lds_cptr)(uintptr_t)(lds_offset(ktt) + tr_off[d][1]);
+        }
         // operand of slot m: m < 16 -> K (even) / V (odd) rows of the next half-block, ks = m / 2;
         // else token-minor K: (16-key group, channel block)
         auto read_operand = [&](auto mc) {
             constexpr int mm = decltype(mc)::value;
             if constexpr (mm < 16) {
-                if constexpr ((mm & 1) == 0) opnd[mm] = rm_operand(kt_, krow0 + n, mm >> 1, h);
-                else opnd[mm] = rm_operand(vt_, krow0 + n, mm >> 1, h);
-            } else if constexpr (mm < 24) {
-                opnd[mm] = tm_operand<kBK>(ktt, ((mm - 16) & 3) * 32 + n, 2 * KB + ((mm - 16) >> 2), h);
+                if constexpr ((mm & 1) == 0) opnd[mm] = rm_tr_row_operand(kt_, krow0 + n, mm >> 1, h);
+                else opnd[mm] = rm_tr_row_operand(vt_, krow0 + n, mm >> 1, h);
+            } else if constexpr (mm < 24) {  // this block's K tile read transposed: channel block, 16-key group
+                constexpr int d = (mm - 16) & 3;
+                opnd[mm] = rm_tr_col_operand_at(trp[d][0], trp[d][1], 2 * KB + ((mm - 16) >> 2), 0);
             }
         };
         auto issue = [&](auto mc) {
@@ -256,13 +255,12 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     SdP Xa, Xb;
     load_kv(jb0, 0);
     if (jb0 < jb1) load_kv(jb0 + 1, 1);
-    load_kt(jb0, 0);
     dma_wait();
     __syncthreads();
     {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 ka = rm_operand(&lds_k[0][0], n, ks, h), va = rm_operand(&lds_v[0][0], n, ks, h);
+            const bf16x8 ka = rm_tr_row_operand(&lds_k[0][0], n, ks, h), va = rm_tr_row_operand(&lds_v[0][0], n, ks, h);
             if (ks == 0) {
                 mfma32_vgpr_first(Xa.s, ka, qreg[ks]);
                 mfma32_vgpr_from(Xa.dp, va, greg[ks], ndl16);
@@ -282,9 +280,9 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
             // prefetch: K, V of block jb+2 (their buffer held block jb-1) and token-minor K of block jb+1
             // (held block jb-1), issued in the slots of the first half-block where the VALU has nothing
             // to do.  Past the last block the last one is loaded again, into buffers nobody reads any more.
-            const int jk = min(jb + 2, jb1), jt = min(jb + 1, jb1);
+            const int jk = min(jb + 2, jb1);
             {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
-                const __bf16* ktt = &lds_kt[rel & 1][0];
+                const __bf16* ktt = &lds_k[buf][0];  // this block's K, read transposed for dQ += dS K
                 BlockLoads L;
                 half_block(mask_tag, Int<0>{}, Xa, Xb, &lds_k[buf][0], &lds_v[buf][0], 32, ktt, jb * kBK, [&](auto mc) {
                     constexpr int mm = decltype(mc)::value;
@@ -292,13 +290,11 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
                         const size_t src = (size_t)jk * kBK * kv_row_bytes;
                         L.ksrc = kbase + src;
                         L.vsrc = vbase + src;
-                        L.ktsrc = ktbase + (size_t)jt * kBK * 2;
                         L.kdst = lds_k0 + buf2 * (kBK * 256);
                         L.vdst = lds_v0 + buf2 * (kBK * 256);
-                        L.ktdst = lds_kt0 + ((rel + 1) & 1) * (kD * kBK * 2);
                         L.krows = min(kBK, gm.T - jk * kBK);
                     }
-                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 3 * kNL) issue_block_load(L, Int<mm - kLoadSlot0>{});
+                    if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 2 * kNL) issue_block_load(L, Int<mm - kLoadSlot0>{});
                 });
                 half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], &lds_v[buf1][0], 0, ktt, jb * kBK + 32,
                            [](auto) {});

@@ -147,15 +147,16 @@ __device__ __forceinline__ void rm_dma_issue(const RmDma<ROWS, NW>& d, const voi
 
 // The same tile when only the first `rows_valid` rows exist in memory: later rows repeat the last
 // valid one (their contents never matter to the caller).  Per-lane arithmetic; for ragged ends only.
-template <int ROWS, int NW = 4>
+// TR: the chunk permutation for transposed reads (rm_tr_swizzle) instead of the plain one.
+template <int ROWS, int NW = 4, bool TR = false>
 __device__ __forceinline__ void rm_dma_issue_clamped(unsigned row_stride_bytes, int rows_valid, const void* sbase,
                                                      unsigned lds_base, int wave) {
     const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int i = 0; i < ROWS / (4 * NW); ++i) {
         const int row = (i * NW + wave) * 4 + (lane >> 4);
-        const unsigned voff =
-            (unsigned)min(row, rows_valid - 1) * row_stride_bytes + (unsigned)(((lane & 15) ^ (row & 15)) * 16);
+        const int sw = TR ? (((row & 3) << 2) | ((row >> 2) & 3)) : (row & 15);
+        const unsigned voff = (unsigned)min(row, rows_valid - 1) * row_stride_bytes + (unsigned)(((lane & 15) ^ sw) * 16);
         dma16_so(sbase, voff, lds_base + (i * NW + wave) * 1024);
     }
 }
