@@ -81,10 +81,9 @@ const char* l2a_strerror(int code);
  *   forward   bf16, D = 128 without L2A_FLAG_SCALAR: a token-minor copy [B,Hkv,D,ceil64(T)] of
  *             each branch's V and one int32 flag per tile of 256 rows (tiles per (b, KV head)
  *             rounded up to a multiple of 8); else nothing
- *   backward  delta_t of each branch, [B,Hq,T] float, twice; on the matrix-core path also a
- *             token-minor copy of each branch's K and, per branch, compact copies of the rows'
- *             Q and dO (row-major and token-minor, ceil64(T G) rows per (b, KV head)) with
- *             three per-row statistics
+ *   backward  delta_t of each branch, [B,Hq,T] float, twice; on the matrix-core path also, per
+ *             branch, compact row-major copies of the rows' Q and dO (ceil64(T G) rows per
+ *             (b, KV head)) with three per-row statistics
  */
 size_t l2a_route_workspace_bytes(const l2a_params* p);
 size_t l2a_attn_workspace_bytes(const l2a_params* p, int backward);

@@ -42,8 +42,6 @@ using Int = std::integral_constant<int, V>;
 struct PackedRows {   // compact copies of one branch's rows, per (b, kv head): cap rows
     const char* qc;      // [nbh][cap][128] bf16
     const char* gc;      // dO
-    const char* qt;      // [nbh][128][cap] bf16, token-minor
-    const char* gt;
     const char* lse2;    // [nbh][cap] f32  lse * log2(e)
     const char* ndelta;  // [nbh][cap] f32  -delta
     const char* pos;     // [nbh][cap] i32, -1 = padding
@@ -447,23 +445,21 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
 
 }  // namespace
 
-// packed[s]: compact copies of set s made by pack_rows (7 pointers in the order of PackedRows).
+// packed[s]: compact copies of set s made by pack_rows (5 pointers in the order of PackedRows).
 // With two sets every array of the second must lie the same number of bytes after the first's.
-int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[7], int cap,
+int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[5], int cap,
                   const void* k, const void* v, void* dk, void* dv, hipStream_t st) {
     if (g.D != kD) return L2A_ERR_UNSUPPORTED;
-    if ((unsigned long long)cap * 2ull * (kD - 1) + 64ull * kRT > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
     DkdvArgs a{};
     a.gm = g;
     a.nsets = nsets;
     a.cap = cap;
     for (int i = 0; i < nsets; ++i) a.rs[i] = sets[i];
     a.rows = PackedRows{(const char*)packed[0][0], (const char*)packed[0][1], (const char*)packed[0][2],
-                        (const char*)packed[0][3], (const char*)packed[0][4], (const char*)packed[0][5],
-                        (const char*)packed[0][6]};
+                        (const char*)packed[0][3], (const char*)packed[0][4]};
     if (nsets > 1) {
         a.set_stride = (const char*)packed[1][0] - (const char*)packed[0][0];
-        for (int j = 1; j < 7; ++j)
+        for (int j = 1; j < 5; ++j)
             if ((const char*)packed[1][j] - (const char*)packed[0][j] != a.set_stride) return L2A_ERR_SHAPE;
     }
     a.k = (const __bf16*)k;

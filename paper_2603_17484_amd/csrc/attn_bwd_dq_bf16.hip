@@ -9,8 +9,9 @@
 // x 32 rows), a lane owns a row, everything is computed transposed:
 //   S^T  = K Q^T        A = K block (LDS),            B = Q  (registers)
 //   dP^T = V dO^T       A = V block (LDS),            B = dO (registers)
-//   dQ^T += K^T dS^T    A = K block, token-minor (LDS), B = dS^T = the accumulators above
-// K, V and the token-minor copy of K stream through LDS by direct global->LDS loads.
+//   dQ^T += K^T dS^T    A = K block read transposed (LDS), B = dS^T = the accumulators above
+// K and V stream through LDS by direct global->LDS loads; one K tile serves both orientations
+// (ds_read_b64_tr_b16 for the second, with a chunk permutation that keeps both free of bank conflicts).
 // Software pipeline per 32 keys (24 matrix-core instructions = 24 slots): the scores of the next
 // half-block (slots 0-15) and the dQ update of this one (slots 16-23) run on the matrix cores
 // while the VALU turns this half-block's S, dP into dS.
@@ -34,8 +35,6 @@ struct DqArgs {
     const __bf16* q;
     const __bf16* k;
     const __bf16* v;
-    const __bf16* kt;  // token-minor copy of K: [B*Hkv][128][kt_cap]
-    int kt_cap;
     const __bf16* dO;
     const float* lse;
     float* delta;  // in: <dO, saved out>; out: sum_j P dP
@@ -336,14 +335,13 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
 
 }  // namespace
 
-int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* kt,
-                int kt_cap, const void* dO, const float* lse, float* delta, void* dq, int accumulate,
-                hipStream_t st) {
+int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,
+                const float* lse, float* delta, void* dq, int accumulate, hipStream_t st) {
     if (g.D != kD) return L2A_ERR_UNSUPPORTED;
-    // per-lane load offsets are 32-bit
-    if ((unsigned long long)kt_cap * 2ull * kD > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
-    DqArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)kt, kt_cap,
-             (const __bf16*)dO, lse, delta, (__bf16*)dq, accumulate};
+    // per-lane load offsets are 32-bit: 64 rows of K or V
+    if (64ull * g.Hkv * kD * 2ull > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
+    DqArgs a{g, rs, (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dO, lse, delta,
+             (__bf16*)dq, accumulate};
     const long long rows = (long long)g.T * g.G;
     constexpr int kNwLocal = 4, kNwGlobal = 8;
     const int bq = (rs.local ? kNwLocal : kNwGlobal) * kRW;

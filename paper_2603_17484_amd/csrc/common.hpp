@@ -95,14 +95,11 @@ int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, cons
 // ---- pack.hip : layout pre-passes (token-minor copies for the matrix-core kernels)
 int pack_kv(const Geom& g, const void* x, void* xt, int cap, hipStream_t st);
 int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, const float* lse, const float* delta,
-              void* qc, void* gc, void* qt, void* gt, float* lse2_c, float* delta_c, int32_t* pos_c, int cap,
-              hipStream_t st);
-// kt: token-minor copy of k from pack_kv
-int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* kt,
-                int kt_cap, const void* dO, const float* lse, float* delta, void* dq, int accumulate,
-                hipStream_t st);
-// packed[s]: the seven outputs of pack_rows for set s (qc, gc, qt, gt, lse2_c, delta_c, pos_c)
-int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[7], int cap,
+              void* qc, void* gc, float* lse2_c, float* delta_c, int32_t* pos_c, int cap, hipStream_t st);
+int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,
+                const float* lse, float* delta, void* dq, int accumulate, hipStream_t st);
+// packed[s]: the five outputs of pack_rows for set s (qc, gc, lse2_c, delta_c, pos_c)
+int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[5], int cap,
                   const void* k, const void* v, void* dk, void* dv, hipStream_t st);
 
 }  // namespace l2a

@@ -52,15 +52,15 @@ size_t redo_bytes(const l2a_params& p) {
 }
 // two token-minor copies of V (one per branch) and the forward kernels' redo flags
 size_t fwd_workspace_bytes(const l2a_params& p) { return use_mfma(p) ? 2 * kv_copy_bytes(p) + redo_bytes(p) : 0; }
-// backward: delta of each branch; matrix-core path: + token-minor copies of K (one per branch)
+// backward: delta of each branch; matrix-core path: + compact copies of each branch's rows
 size_t delta_bytes(const l2a_params& p) { return (sizeof(float) * stat_elems(p) + 255) / 256 * 256; }
-// compact copies of a branch's rows for the dK/dV kernel: Q, dO row-major and token-minor, + 3 statistics
+// compact copies of a branch's rows for the dK/dV kernel: Q, dO row-major, + 3 statistics
 int rows_cap(const l2a_params& p) { return (int)(((long long)p.T * (p.Hq / p.Hkv) + 63) / 64 * 64); }
 size_t rows_copy_bytes(const l2a_params& p) { return (size_t)p.B * p.Hkv * rows_cap(p) * p.D * 2; }
 size_t rows_stat_bytes(const l2a_params& p) { return ((size_t)p.B * p.Hkv * rows_cap(p) * 4 + 255) / 256 * 256; }
-size_t packed_set_bytes(const l2a_params& p) { return 4 * rows_copy_bytes(p) + 3 * rows_stat_bytes(p); }
+size_t packed_set_bytes(const l2a_params& p) { return 2 * rows_copy_bytes(p) + 3 * rows_stat_bytes(p); }
 size_t bwd_workspace_bytes(const l2a_params& p) {
-    return 2 * delta_bytes(p) + (use_mfma(p) ? 2 * kv_copy_bytes(p) + 2 * packed_set_bytes(p) : 0);
+    return 2 * delta_bytes(p) + (use_mfma(p) ? 2 * packed_set_bytes(p) : 0);
 }
 
 
@@ -242,18 +242,9 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
     float* delta_l = (float*)workspace;
     float* delta_g = delta_glb_opt ? delta_glb_opt : (float*)((char*)workspace + delta_bytes(*p));
     const bool mfma = use_mfma(*p);
-    char* kt_loc = (char*)workspace + 2 * delta_bytes(*p);
-    char* kt_glb = kt_loc;
-    if (mfma) {  // token-minor copy of each distinct K (layout pre-pass)
-        if (do_local && (r = pack_kv(g, k_loc, kt_loc, kv_cap(*p), st)) != L2A_OK) return r;
-        if (do_global && (!do_local || k_glb != k_loc)) {
-            kt_glb = kt_loc + kv_copy_bytes(*p);
-            if ((r = pack_kv(g, k_glb, kt_glb, kv_cap(*p), st)) != L2A_OK) return r;
-        }
-    }
-    auto bwd_dq = [&](const RowSet& rs, const void* q, const void* k, const void* v, const void* kt, const float* lse,
-                      float* delta, void* dq, int acc) {
-        return mfma ? mfma_bwd_dq(g, rs, q, k, v, kt, kv_cap(*p), dO, lse, delta, dq, acc, st)
+    auto bwd_dq = [&](const RowSet& rs, const void* q, const void* k, const void* v, const float* lse, float* delta,
+                      void* dq, int acc) {
+        return mfma ? mfma_bwd_dq(g, rs, q, k, v, dO, lse, delta, dq, acc, st)
                     : simple_bwd_dq(g, p->dtype, rs, q, k, v, dO, lse, delta, dq, acc, st);
     };
     if ((r = row_deltas(g, p->dtype, dO, do_local ? S : nullptr, do_global ? A : nullptr, delta_l, delta_g, st)) !=
@@ -264,30 +255,29 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
     const RowSet rs_g = dense ? RowSet{nullptr, nullptr, nullptr, 0} : RowSet{row_idx, count, kblk_first_row, 0};
 
     // dQ: one pass per branch over that branch's rows
-    if (do_local && (r = bwd_dq(rs_l, q_loc, k_loc, v_loc, kt_loc, lse_local, delta_l, dq_loc, 0)) != L2A_OK) return r;
+    if (do_local && (r = bwd_dq(rs_l, q_loc, k_loc, v_loc, lse_local, delta_l, dq_loc, 0)) != L2A_OK) return r;
     if (do_global) {
         if (!out_alias && !dense && (r = fill_zero(dq_glb, q_elems(*p) * elem_bytes(*p), st)) != L2A_OK) return r;
-        if ((r = bwd_dq(rs_g, q_glb, k_glb, v_glb, kt_glb, lse_global, delta_g, dq_glb, out_alias ? 1 : 0)) != L2A_OK)
+        if ((r = bwd_dq(rs_g, q_glb, k_glb, v_glb, lse_global, delta_g, dq_glb, out_alias ? 1 : 0)) != L2A_OK)
             return r;
     }
     // dK, dV: one pass over the key tokens; with shared inputs both branches accumulate in registers.
     // The matrix-core kernel reads each branch's rows from compact copies (layout pre-pass).
-    char* packed_base = (char*)workspace + 2 * delta_bytes(*p) + 2 * kv_copy_bytes(*p);
+    char* packed_base = (char*)workspace + 2 * delta_bytes(*p);
     const int cap = rows_cap(*p);
     auto dkdv = [&](const RowSet* sets, int n, const void* const* qs, const float* const* lses,
                     const float* const* deltas, const void* k, const void* v, void* dk, void* dv) -> int {
         if (!mfma) return simple_bwd_dkdv(g, p->dtype, sets, n, qs[0], k, v, dO, lses, deltas, dk, dv, st);
-        const void* packed[2][7];
+        const void* packed[2][5];
         for (int i = 0; i < n; ++i) {
             char* base = packed_base + (sets[i].local ? 0 : packed_set_bytes(*p));
-            char* stat = base + 4 * rows_copy_bytes(*p);
-            void* out[7] = {base, base + rows_copy_bytes(*p), base + 2 * rows_copy_bytes(*p),
-                            base + 3 * rows_copy_bytes(*p), stat, stat + rows_stat_bytes(*p),
+            char* stat = base + 2 * rows_copy_bytes(*p);
+            void* out[5] = {base, base + rows_copy_bytes(*p), stat, stat + rows_stat_bytes(*p),
                             stat + 2 * rows_stat_bytes(*p)};
-            const int rc2 = pack_rows(g, sets[i], qs[i], dO, lses[i], deltas[i], out[0], out[1], out[2], out[3],
-                                      (float*)out[4], (float*)out[5], (int32_t*)out[6], cap, st);
+            const int rc2 = pack_rows(g, sets[i], qs[i], dO, lses[i], deltas[i], out[0], out[1], (float*)out[2],
+                                      (float*)out[3], (int32_t*)out[4], cap, st);
             if (rc2 != L2A_OK) return rc2;
-            for (int j = 0; j < 7; ++j) packed[i][j] = out[j];
+            for (int j = 0; j < 5; ++j) packed[i][j] = out[j];
         }
         return mfma_bwd_dkdv(g, sets, n, packed, cap, k, v, dk, dv, st);
     };

@@ -1,12 +1,12 @@
 // Layout pre-passes of the matrix-core kernels (memory-bound, one pass over the tensor).
 //
-//   pack_token_minor : writes the token-minor copy XT[b, kv head, channel, row] of a tensor whose
-//                      rows are either the tokens of a KV head (K, V) or the rows of a branch's
-//                      row set -- for the Global branch this is the consolidation of the active
-//                      queries into a contiguous buffer Q_c (App. C Alg. 1 step 1), done for Q and
-//                      dO, together with the rows' saved statistics.  Rows inside each group of
-//                      16 are stored in the order the matrix-core operands want (tiles.hpp).
-//                      Optionally also writes the compact row-major copy.
+//   pack_token_minor : copies of a tensor whose rows are either the tokens of a KV head (V, for
+//                      the forward kernel: the token-minor copy XT[b, kv head, channel, row], rows
+//                      inside each group of 16 in the order the matrix-core operands want, see
+//                      tiles.hpp) or the rows of a branch's row set (Q and dO, for the dK/dV
+//                      kernel: compact row-major copies together with the rows' saved statistics
+//                      -- for the Global branch this is the consolidation of the active queries
+//                      into a contiguous buffer Q_c, App. C Alg. 1 step 1).
 // The transpose itself is done by ds_read_b64_tr_b16: sixteen lanes hand in four rows of sixteen
 // channels and each lane gets back four rows of one channel.
 #include "tiles.hpp"
@@ -22,7 +22,7 @@ struct PackArgs {
     RowSet rs;
     int kv_rows;  // 1: rows are the tokens of a KV head, tensors are [B,T,Hkv,D]; 0: rows of rs, tensors [B,T,Hq,D]
     const __bf16* x[2];   // up to two tensors share the row list (Q and dO); x[1] may be null
-    __bf16* xt[2];        // token-minor copies [B*Hkv][128][cap]
+    __bf16* xt[2];        // optional token-minor copies [B*Hkv][128][cap]
     __bf16* xc[2];        // optional compact row-major copies [B*Hkv][cap][128]
     const float* lse;     // optional per-row statistics of the row set, [B,Hq,T]
     const float* delta;
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kThreads) void pack_token_minor_kernel(PackArgs a) 
         for (int i = 0; i < 4; ++i) {
             u32x4 v = {0u, 0u, 0u, 0u};
             if (offs[i] >= 0) v = *reinterpret_cast<const u32x4*>(a.x[t] + offs[i] + c8);
-            *reinterpret_cast<u32x4*>(&lds[t][(r4 + i) * kRowPad + c8]) = v;
+            if (a.xt[t]) *reinterpret_cast<u32x4*>(&lds[t][(r4 + i) * kRowPad + c8]) = v;
             if (a.xc[t])
                 *reinterpret_cast<u32x4*>(a.xc[t] + ((size_t)bh * a.cap + r0 + r4 + i) * kD + c8) = v;
         }
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void pack_token_minor_kernel(PackArgs a) 
     const int j = lane & 15, gi = lane >> 4;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-        if (!a.x[t]) continue;
+        if (!a.x[t] || !a.xt[t]) continue;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
             const int combo = (wave * 4 + tt) * 4 + gi;
@@ -121,18 +121,15 @@ int pack_kv(const Geom& g, const void* x, void* xt, int cap, hipStream_t st) {
     return launch_status();
 }
 
-// rows of a branch: Q and dO -> compact row-major and token-minor copies + per-row statistics
+// rows of a branch: Q and dO -> compact row-major copies + per-row statistics
 int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, const float* lse, const float* delta,
-              void* qc, void* gc, void* qt, void* gt, float* lse2_c, float* delta_c, int32_t* pos_c, int cap,
-              hipStream_t st) {
+              void* qc, void* gc, float* lse2_c, float* delta_c, int32_t* pos_c, int cap, hipStream_t st) {
     PackArgs a{};
     a.gm = g;
     a.rs = rs;
     a.kv_rows = 0;
     a.x[0] = (const __bf16*)q;
     a.x[1] = (const __bf16*)dO;
-    a.xt[0] = (__bf16*)qt;
-    a.xt[1] = (__bf16*)gt;
     a.xc[0] = (__bf16*)qc;
     a.xc[1] = (__bf16*)gc;
     a.lse = lse;

@@ -48,9 +48,9 @@ def test_workspace_queries(lib):
     redo = up(4 * up(up(T * G, 256) // 256, 8) * Bn * Hkv, 256)   # tiles per (b, KV head): a multiple of 8
     delta = up(4 * Bn * Hq * T, 256)
     cap = up(T * G, 64)
-    packed = 4 * (Bn * Hkv * cap * D * 2) + 3 * up(Bn * Hkv * cap * 4, 256)
+    packed = 2 * (Bn * Hkv * cap * D * 2) + 3 * up(Bn * Hkv * cap * 4, 256)   # Q, dO rows + 3 statistics
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 0) == 2 * kv_copy + redo
-    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta + 2 * kv_copy + 2 * packed
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta + 2 * packed
     p.flags = B.L2A_FLAG_SCALAR   # scalar kernels: only the two delta arrays
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 0) == 0
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta
