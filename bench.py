@@ -28,8 +28,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 # FETCH x 2.0, WRITE x 1.0.  The counters cannot be read from inside the process, so the figures of the
 # committed profile are repeated here; they are reported only for exactly that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "bwd_dkdv": 7.585e10, "bwd_dq_global": 3.811e10, "bwd_dq_local": 3.063e10,
-    "fwd_global": 1.484e10, "fwd_local": 2.809e10,
+    "bwd_dkdv": 1.851e10, "bwd_dq_global": 1.769e10, "bwd_dq_local": 4.26e9,
+    "fwd_global": 1.484e10, "fwd_local": 5.24e9,
 }
 
 
