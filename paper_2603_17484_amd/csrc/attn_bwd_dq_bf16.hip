@@ -67,9 +67,11 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     // rows: longest prefixes first; every tile starts at key block 0, so the tiles resident on an XCD
     // read the same K/V block at about the same time whatever their order.  Local rows: each XCD
     // takes a contiguous range of tiles, so that the tiles resident on it have overlapping windows
-    // and share their K/V blocks through its L2.
+    // and share their K/V blocks through its L2 -- when the sequence is several windows long, so that
+    // the ranges cost the same; otherwise the tiles' costs grow with their position like the Global
+    // ones' and they are ordered the same way.
     int tile;
-    if (LOCAL) {
+    if (LOCAL && gm.T / 4 > gm.W) {
         const int per = (int)gridDim.x >> 3;
         tile = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
     } else {
