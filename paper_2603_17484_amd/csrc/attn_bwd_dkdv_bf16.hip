@@ -31,8 +31,8 @@ constexpr int kRT = 32;     // rows per tile
 constexpr int kAhead = 3;   // operand look-ahead, in slots
 constexpr int kNB = 8;              // LDS buffers: loads run kNB - 1 tiles ahead
 constexpr int kDmaPerStep = 7;      // direct-to-LDS instructions a wavefront issues per tile step
-constexpr int kLoadSlot0 = 1;       // ... in slots kLoadSlot0 + kLoadStride i of a step, i = 0 .. 10: the four wavefronts
-constexpr int kLoadStride = 4;      // issue theirs at about the same time, and the load path takes them one by one
+constexpr int kLoadSlot0 = 1;       // ... in slots kLoadSlot0 + kLoadStride i of a step, i = 0 .. 6
+constexpr int kLoadStride = 4;
 
 #define L2A_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         }
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    // One tile: P, dS from `cur` (tile it; statistics and token-minor tiles in ct) overlapped with
+    // One tile: P, dS from `cur` (tile it; its statistics and, read transposed, its rows in ct) overlapped with
     // S, dP of tile it+1 into `nxt` (row-major tiles rt) and the dV, dK update of tile it.
     auto tile_step = [&](auto mask_tag, SdP& cur, SdP& nxt, const RowTileLds& rt, const RowTileLds& ct, bool local,
                          auto&& stage_loads, auto&& loads_issued) __attribute__((always_inline)) {
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             if (MASK) ps[rg] = *reinterpret_cast<const i32x4*>(&ct.pos[8 * rg + 4 * h]);
         }
         // operand of slot m: m < 16 -> Q (even) / dO (odd) rows of the next tile, ks = m / 2;
-        // else token-minor dO (even) / Q (odd): 16-row group (m - 16) / 8, channel block ((m - 16) / 2) % 4
+        // else dO (even) / Q (odd) of this tile read transposed: 16-row group (m - 16) / 8, channel block ((m - 16) / 2) % 4
         auto read_operand = [&](auto mc) {
             constexpr int mm = decltype(mc)::value;
             if constexpr (mm < 16) {

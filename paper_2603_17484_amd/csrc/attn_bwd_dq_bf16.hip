@@ -187,7 +187,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
             trp[d][1] = (lds_cptr)(uintptr_t)(lds_offset(ktt) + tr_off[d][1]);
         }
         // operand of slot m: m < 16 -> K (even) / V (odd) rows of the next half-block, ks = m / 2;
-        // else token-minor K: (16-key group, channel block)
+        // else this block's K read transposed: (16-key group, channel block)
         auto read_operand = [&](auto mc) {
             constexpr int mm = decltype(mc)::value;
             if constexpr (mm < 16) {
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
         dlt_exact += dsum;
     };
 
-    // ---- prologue: K, V of the first two blocks, token-minor K of the first; S, dP of the first half-block
+    // ---- prologue: K, V of the first two blocks; S, dP of the first half-block
     SdP Xa, Xb;
     load_kv(jb0, 0);
     if (jb0 < jb1) load_kv(jb0 + 1, 1);
@@ -278,9 +278,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     auto run = [&](auto mask_tag, int j_begin, int j_end) __attribute__((always_inline)) {
         for (int jb = j_begin; jb < j_end; ++jb) {
             const int rel = jb - jb0;
-            // prefetch: K, V of block jb+2 (their buffer held block jb-1) and token-minor K of block jb+1
-            // (held block jb-1), issued in the slots of the first half-block where the VALU has nothing
-            // to do.  Past the last block the last one is loaded again, into buffers nobody reads any more.
+            // prefetch: K, V of block jb+2 (their buffer held block jb-1), issued in the slots of the first
+            // half-block where the VALU has nothing to do.  Past the last block the last one is loaded again, into buffers nobody reads any more.
             const int jk = min(jb + 2, jb1);
             {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
                 const __bf16* ktt = &lds_k[buf][0];  // this block's K, read transposed for dQ += dS K
