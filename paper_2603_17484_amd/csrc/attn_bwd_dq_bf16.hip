@@ -277,7 +277,6 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     int buf = 0, buf1 = 1, buf2 = 2;
     auto run = [&](auto mask_tag, int j_begin, int j_end) __attribute__((always_inline)) {
         for (int jb = j_begin; jb < j_end; ++jb) {
-            const int rel = jb - jb0;
             // prefetch: K, V of block jb+2 (their buffer held block jb-1), issued in the slots of the first
             // half-block where the VALU has nothing to do.  Past the last block the last one is loaded again, into buffers nobody reads any more.
             const int jk = min(jb + 2, jb1);

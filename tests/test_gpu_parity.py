@@ -270,7 +270,7 @@ def test_bf16_scores_falling_along_sequence(oracle):
     run_and_check(oracle, growing_scores_case(-40.0))
 
 
-@pytest.mark.parametrize("T,Hq,Hkv", [(129, 7, 1), (193, 3, 1), (2049, 2, 2), (4100, 14, 2)])
+@pytest.mark.parametrize("T,Hq,Hkv", [(129, 7, 1), (193, 3, 1), (2049, 2, 2), (4100, 14, 2), (300, 16, 1)])
 def test_bf16_ragged_tiles(oracle, T, Hq, Hkv):
     """Row counts and key counts just past tile boundaries; T * G not a multiple of the row tile."""
     run_and_check(oracle, make_case(T=T, Hq=Hq, Hkv=Hkv, W=70, f=0.35, seed=50 + T % 13))
