@@ -221,6 +221,7 @@ def main() -> int:
         "fwd_local": 4.0 * D * pl, "fwd_global": 4.0 * D * pg,
         "bwd_dq_local": 2.0 * D * pl, "bwd_dq_global": 2.0 * D * pg,
         "bwd_dkdv": 8.0 * D * (pl + pg),
+        "fwd_pair": 4.0 * D * (pl + pg),   # short sequences: both branches of the forward in one launch
     }
     dom = max((n for n in kern if n in alg), key=lambda n: kern[n])
     achieved = alg[dom] / (kern[dom] * 1e-3) / 1e12

@@ -46,6 +46,8 @@ enum {
                                  FlashAttention-style mode; mask and index arrays are ignored, may be NULL */
     L2A_FLAG_SKIP_LOCAL = 2,  /* run the Global branch only:  O = d a  */
     L2A_FLAG_SKIP_GLOBAL = 4, /* run the Local branch only:   O = s    */
+    L2A_FLAG_SEQUENTIAL = 8,  /* forward: run the branches one after the other at every length (see
+                                 l2a_attn_fwd: short sequences otherwise run them in one launch) */
     L2A_FLAG_SCALAR = 1 << 16 /* bf16 only: use the scalar-FMA kernels instead of the matrix-core ones
                                  (slow; for cross-checking) */
 };
@@ -80,7 +82,8 @@ const char* l2a_strerror(int code);
  *   route     one int32 count per (b, mask head, 2048-position chunk)
  *   forward   bf16, D = 128 without L2A_FLAG_SCALAR: a token-minor copy [B,Hkv,D,ceil64(T)] of
  *             each branch's V and one int32 flag per tile of 256 rows (tiles per (b, KV head)
- *             rounded up to a multiple of 8); else nothing
+ *             rounded up to a multiple of 8); when both branches run in one launch (see
+ *             l2a_attn_fwd) the flags twice and a [B,T,Hq,D] float buffer for a; else nothing
  *   backward  delta_t of each branch, [B,Hq,T] float, twice; on the matrix-core path also, per
  *             branch, compact row-major copies of the rows' Q and dO (ceil64(T G) rows per
  *             (b, KV head)) with three per-row statistics
@@ -143,6 +146,13 @@ int l2a_router_decide(const l2a_params* p, int32_t C, const void* x, const float
  *   lse_global  out [B,Hq,T]    -inf where d = 0 (may be NULL with L2A_FLAG_SKIP_GLOBAL)
  *   S_opt       out optional [B,T,Hq,D]: s alone (needed by l2a_attn_bwd)
  *   A_opt       out optional [B,T,Hq,D]: d a alone, zero where d = 0 (needed by l2a_attn_bwd)
+ *
+ * Short sequences (bf16, D = 128, both branches, routing lists in use, at most 2048 tiles of 256
+ * rows over all (b, KV head)): the Global rows' tiles alone would occupy a fraction of the chip, so
+ * the two branches run in one launch, the Global one leaves a in fp32 in the workspace, and a
+ * third, small kernel forms o = s + d a -- bit for bit the result of the sequential order, where
+ * the Global kernel adds its fp32 result to the stored s.  L2A_FLAG_SEQUENTIAL keeps the sequential
+ * order at every length.
  */
 int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, const void* v_loc,
                  const void* q_glb, const void* k_glb, const void* v_glb, const int32_t* row_idx,

@@ -60,23 +60,29 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     __shared__ __attribute__((aligned(1024))) __bf16 lds_v[3][kBK * 128];
 
     const Geom& gm = a.gm;
-    const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
-    const int n_rows = rows_total(a.rs, gm, bh);
-    const int n_tiles = (n_rows + kBQ - 1) / kBQ;
-    // Workgroups are dealt round-robin to the 8 XCDs (the grid's width is a multiple of 8).  Global
-    // rows: longest prefixes first; every tile starts at key block 0, so the tiles resident on an XCD
-    // read the same K/V block at about the same time whatever their order.  Local rows: each XCD
-    // takes a contiguous range of tiles, so that the tiles resident on it have overlapping windows
+    // Workgroups are dispatched in the order of their linear index and dealt round-robin to the 8 XCDs
+    // (the grid's width is a multiple of 8).  Global rows: longest prefixes first, over all (b, KV
+    // head) together -- with a few hundred tiles in all, a head whose long tiles started last would
+    // set the kernel's time; every tile starts at key block 0, so the tiles resident on an XCD read
+    // the same K/V blocks at about the same time whatever their order.  Local rows: each XCD takes
+    // a contiguous range of a head's tiles, so that the tiles resident on it have overlapping windows
     // and share their K/V blocks through its L2 -- when the sequence is several windows long, so that
     // the ranges cost the same; otherwise the tiles' costs grow with their position like the Global
     // ones' and they are ordered the same way.
-    int tile;
-    if (LOCAL && gm.T / 4 > gm.W) {
-        const int per = (int)gridDim.x >> 3;
-        tile = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+    int bh, rank;
+    const bool by_range = LOCAL && gm.T / 4 > gm.W;
+    if (by_range) {
+        bh = blockIdx.y;
+        rank = ((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3);
     } else {
-        tile = n_tiles - 1 - (int)blockIdx.x;
+        const int lin = (int)(blockIdx.y * gridDim.x + blockIdx.x);
+        rank = lin / (int)gridDim.y;
+        bh = lin - rank * (int)gridDim.y;
     }
+    const int b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
+    const int n_rows = rows_total(a.rs, gm, bh);
+    const int n_tiles = (n_rows + kBQ - 1) / kBQ;
+    const int tile = by_range ? rank : n_tiles - 1 - rank;
     if (tile < 0 || tile >= n_tiles) return;
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

@@ -61,35 +61,41 @@ using Int = std::integral_constant<int, V>;
 // NW wavefronts of NQB x 32 rows each (NW * NQB = 8): 4 x 2 runs one wavefront per SIMD with 500 registers,
 // 8 x 1 runs two per SIMD with 256 each, so that one wavefront's softmax arithmetic can overlap the
 // other's matrix instructions.
+// (bx, by) of (gx, nbh): the workgroup's index in its branch's part of the grid (a launch may carry both branches)
 template <bool LOCAL, int NQB, int NW>
-__global__ __launch_bounds__(64 * NW) void fwd_kernel(FwdArgs a) {
+__device__ __forceinline__ void fwd_body(const FwdArgs& a, const int bx, const int by, const int gx, const int nbh,
+                                         __bf16 (&lds_k)[3][kBK * 128], __bf16 (&lds_v)[2][kD * kBK]) {
     static_assert(NW * NQB * 32 == kBQ, "a workgroup covers kBQ rows");
     constexpr int RW = 32 * NQB;       // rows per wavefront
     constexpr int NS = 16 * NQB;       // slots (matrix instructions) per half-block: NS / 2 for S, NS / 2 for P V
     constexpr int NL = 16 / NW;        // 16-byte loads a wavefront issues per K or V block
     constexpr int kLoadSlot0 = NS - 1 - 2 * NL;  // the loads of later blocks go out in the last slots of a block's first half
     using Scores = ScoresT<NQB>;
-    __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
-    __shared__ __attribute__((aligned(1024))) __bf16 lds_v[2][kD * kBK];
 
     const Geom& gm = a.gm;
-    const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
-    const int n_rows = rows_total(a.rs, gm, bh);
-    const int n_tiles = (n_rows + kBQ - 1) / kBQ;
-    // Workgroups are dealt round-robin to the 8 XCDs (the grid's width is a multiple of 8).  Global
-    // rows: longest prefixes first; every tile starts at key block 0, so the tiles resident on an XCD
-    // read the same K/V block at about the same time whatever their order.  Local rows: each XCD
-    // takes a contiguous range of tiles, so that the tiles resident on it have overlapping windows
+    // Workgroups are dispatched in the order of their linear index and dealt round-robin to the 8 XCDs
+    // (the grid's width is a multiple of 8).  Global rows: longest prefixes first, over all (b, KV
+    // head) together -- with a few hundred tiles in all, a head whose long tiles started last would
+    // set the kernel's time; every tile starts at key block 0, so the tiles resident on an XCD read
+    // the same K/V blocks at about the same time whatever their order.  Local rows: each XCD takes
+    // a contiguous range of a head's tiles, so that the tiles resident on it have overlapping windows
     // and share their K/V blocks through its L2 -- when the sequence is several windows long, so that
     // the ranges cost the same; otherwise the tiles' costs grow with their position like the Global
     // ones' and they are ordered the same way.
-    int tile;
-    if (LOCAL && gm.T / 4 > gm.W) {
-        const int per = (int)gridDim.x >> 3;
-        tile = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+    int bh, rank;
+    const bool by_range = LOCAL && gm.T / 4 > gm.W;
+    if (by_range) {
+        bh = by;
+        rank = (bx & 7) * (gx >> 3) + (bx >> 3);
     } else {
-        tile = n_tiles - 1 - (int)blockIdx.x;
+        const int lin = by * gx + bx;
+        rank = lin / nbh;
+        bh = lin - rank * nbh;
     }
+    const int b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
+    const int n_rows = rows_total(a.rs, gm, bh);
+    const int n_tiles = (n_rows + kBQ - 1) / kBQ;
+    const int tile = by_range ? rank : n_tiles - 1 - rank;
     if (tile < 0 || tile >= n_tiles) return;
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -361,7 +367,7 @@ __global__ __launch_bounds__(64 * NW) void fwd_kernel(FwdArgs a) {
     if (bad) *vote = 1;
     __syncthreads();
     if (*vote) {
-        if (threadIdx.x == 0) a.redo[(size_t)bh * gridDim.x + tile] = 1;
+        if (threadIdx.x == 0) a.redo[(size_t)bh * gx + tile] = 1;
         return;
     }
 
@@ -387,7 +393,8 @@ __global__ __launch_bounds__(64 * NW) void fwd_kernel(FwdArgs a) {
                     const bf16x4 old = *reinterpret_cast<const bf16x4*>(mo + off);
                     x += __builtin_convertvector(old, f32x4);
                 }
-                *reinterpret_cast<bf16x4*>(mo + off) = __builtin_convertvector(x, bf16x4);
+                if (a.out.wide_out) *reinterpret_cast<f32x4*>(a.out.wide_out + off) = x;
+                else *reinterpret_cast<bf16x4*>(mo + off) = __builtin_convertvector(x, bf16x4);
                 if (zf) {
                     const u32x2 z = {0u, 0u};
                     *reinterpret_cast<u32x2*>(zf + off) = z;
@@ -399,6 +406,29 @@ __global__ __launch_bounds__(64 * NW) void fwd_kernel(FwdArgs a) {
             if (a.out.lse_fill) a.out.lse_fill[so] = -INFINITY;
         }
     }
+}
+
+template <bool LOCAL, int NQB, int NW>
+__global__ __launch_bounds__(64 * NW) void fwd_kernel(FwdArgs a) {
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_v[2][kD * kBK];
+    fwd_body<LOCAL, NQB, NW>(a, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.x, (int)gridDim.y, lds_k, lds_v);
+}
+
+// Both branches in one launch, for sequences so short that the Global rows' tiles alone leave most
+// compute units idle: the first gx_global workgroups (per b, KV head) take the Global rows' tiles,
+// the others the Local rows'.  The branches then must not depend on each other: the Global one
+// writes its rows of A only (in fp32, besides the caller's bf16 copy), and O = S + A is formed
+// afterwards (merge_rows) with the one rounding the sequential order has.
+template <int NQB, int NW>
+__global__ __launch_bounds__(64 * NW) void fwd_pair_kernel(FwdArgs ag, FwdArgs al, int gx_global) {
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_v[2][kD * kBK];
+    if ((int)blockIdx.x < gx_global)
+        fwd_body<false, NQB, NW>(ag, (int)blockIdx.x, (int)blockIdx.y, gx_global, (int)gridDim.y, lds_k, lds_v);
+    else
+        fwd_body<true, NQB, NW>(al, (int)blockIdx.x - gx_global, (int)blockIdx.y, (int)gridDim.x - gx_global,
+                                (int)gridDim.y, lds_k, lds_v);
 }
 
 // Fix-up kernel: recomputes the tiles the pipelined kernel gave up on (a later score exceeded a
@@ -612,7 +642,8 @@ __global__ __launch_bounds__(kThreads) void fwd_fixup_kernel(FwdArgs a) {
                     const bf16x4 old = *reinterpret_cast<const bf16x4*>(mo + off);
                     x += __builtin_convertvector(old, f32x4);
                 }
-                *reinterpret_cast<bf16x4*>(mo + off) = __builtin_convertvector(x, bf16x4);
+                if (a.out.wide_out) *reinterpret_cast<f32x4*>(a.out.wide_out + off) = x;
+                else *reinterpret_cast<bf16x4*>(mo + off) = __builtin_convertvector(x, bf16x4);
                 if (zf) {
                     const u32x2 z = {0u, 0u};
                     *reinterpret_cast<u32x2*>(zf + off) = z;
@@ -652,6 +683,37 @@ int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, cons
             hipLaunchKernelGGL((fwd_fixup_kernel<true>), grid, dim3(kThreads), 0, st, a);
         else
             hipLaunchKernelGGL((fwd_fixup_kernel<false>), grid, dim3(kThreads), 0, st, a);
+    }
+    return launch_status();
+}
+
+// Both branches at once (fwd_pair_kernel): the Global branch's result goes to out_g.wide_out, and
+// neither branch may write where the other does.  redo: 2 x mfma_fwd_redo_entries flags.
+int mfma_fwd_pair(const Geom& g, const RowSet& rs_l, const void* q_l, const void* k_l, const void* v_l,
+                  const void* vt_l, const FwdOut& out_l, const RowSet& rs_g, const void* q_g, const void* k_g,
+                  const void* v_g, const void* vt_g, const FwdOut& out_g, int vt_cap, int32_t* redo, hipStream_t st) {
+    if (g.D != kD || out_g.merge || !out_g.wide_out || out_l.wide_out) return L2A_ERR_UNSUPPORTED;
+    if ((unsigned long long)vt_cap * 2ull * kD > 0xffffffffull) return L2A_ERR_UNSUPPORTED;
+    const long long rows = (long long)g.T * g.G;
+    const unsigned gx = (unsigned)(((rows + kBQ - 1) / kBQ + 7) / 8 * 8);  // per branch
+    const size_t entries = (size_t)gx * g.B * g.Hkv;
+    FwdArgs al{g, rs_l, (const __bf16*)q_l, (const __bf16*)k_l, (const __bf16*)v_l, (const __bf16*)vt_l, vt_cap, redo, out_l};
+    FwdArgs ag{g, rs_g, (const __bf16*)q_g, (const __bf16*)k_g, (const __bf16*)v_g, (const __bf16*)vt_g, vt_cap,
+               redo + entries, out_g};
+    int r = fill_zero(redo, sizeof(int32_t) * 2 * entries, st);
+    if (r != L2A_OK) return r;
+    {
+        KernelTimer kt("fwd_pair", st);
+        hipLaunchKernelGGL((fwd_pair_kernel<kFwdNQB, kFwdNW>), dim3(2 * gx, g.B * g.Hkv), dim3(64 * kFwdNW), 0, st, ag, al,
+                           (int)gx);
+    }
+    {
+        KernelTimer kt("fwd_local_fixup", st);
+        hipLaunchKernelGGL((fwd_fixup_kernel<true>), dim3(gx, g.B * g.Hkv), dim3(kThreads), 0, st, al);
+    }
+    {
+        KernelTimer kt("fwd_global_fixup", st);
+        hipLaunchKernelGGL((fwd_fixup_kernel<false>), dim3(gx, g.B * g.Hkv), dim3(kThreads), 0, st, ag);
     }
     return launch_status();
 }

@@ -57,6 +57,7 @@ struct FwdOut {
     float* lse_fill;
     void* zero_fill;
     int merge;
+    float* wide_out = nullptr;  // matrix-core kernels: the result goes here in fp32 instead of to main_out
 };
 
 // ---- attn_simple.hip : straightforward scalar-FMA kernels (fp32 arithmetic, any element type)
@@ -85,6 +86,10 @@ int fill_f32(float* ptr, size_t n, float value, hipStream_t st);
 int mfma_fwd(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* vt,
              int vt_cap, int32_t* redo, const FwdOut& out, hipStream_t st);
 size_t mfma_fwd_redo_entries(const Geom& g);
+// both branches in one launch; out_g must not merge; redo: 2 x mfma_fwd_redo_entries(g) int32
+int mfma_fwd_pair(const Geom& g, const RowSet& rs_l, const void* q_l, const void* k_l, const void* v_l,
+                  const void* vt_l, const FwdOut& out_l, const RowSet& rs_g, const void* q_g, const void* k_g,
+                  const void* v_g, const void* vt_g, const FwdOut& out_g, int vt_cap, int32_t* redo, hipStream_t st);
 
 // ---- attn_decode_bf16.hip : one new token per sequence against the KV cache (bf16, D = 128)
 size_t decode_partial_floats(const Geom& g);
@@ -94,6 +99,8 @@ int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, cons
 
 // ---- pack.hip : layout pre-passes (token-minor copies for the matrix-core kernels)
 int pack_kv(const Geom& g, const void* x, void* xt, int cap, hipStream_t st);
+// O += A on the rows of rs (O bf16, A fp32, D = 128)
+int merge_rows(const Geom& g, const RowSet& rs, const float* A, void* O, hipStream_t st);
 int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, const float* lse, const float* delta,
               void* qc, void* gc, float* lse2_c, float* delta_c, int32_t* pos_c, int cap, hipStream_t st);
 int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,

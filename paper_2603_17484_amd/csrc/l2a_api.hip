@@ -50,8 +50,21 @@ size_t redo_bytes(const l2a_params& p) {
     const size_t n = mfma_fwd_redo_entries(make_geom(p)) * sizeof(int32_t);
     return (n + 255) / 256 * 256;
 }
-// two token-minor copies of V (one per branch) and the forward kernels' redo flags
-size_t fwd_workspace_bytes(const l2a_params& p) { return use_mfma(p) ? 2 * kv_copy_bytes(p) + redo_bytes(p) : 0; }
+// Short sequences: the Global rows' tiles alone would leave most compute units idle, so both
+// branches go out in one launch and O = S + A is formed afterwards.
+constexpr size_t kPairMaxTiles = 2048;  // row tiles of one branch, all (b, KV head) together
+bool pair_fwd(const l2a_params& p) {
+    const int f = p.flags;
+    return use_mfma(p) && !(f & (L2A_FLAG_DENSE | L2A_FLAG_SKIP_LOCAL | L2A_FLAG_SKIP_GLOBAL | L2A_FLAG_SEQUENTIAL)) &&
+           mfma_fwd_redo_entries(make_geom(p)) <= kPairMaxTiles;
+}
+// two token-minor copies of V (one per branch) and the forward kernels' redo flags; short sequences:
+// flags for both branches at once and room for A in fp32
+size_t fwd_workspace_bytes(const l2a_params& p) {
+    if (!use_mfma(p)) return 0;
+    if (pair_fwd(p)) return 2 * kv_copy_bytes(p) + 2 * redo_bytes(p) + q_elems(p) * sizeof(float);
+    return 2 * kv_copy_bytes(p) + redo_bytes(p);
+}
 // backward: delta of each branch; matrix-core path: + compact copies of each branch's rows
 size_t delta_bytes(const l2a_params& p) { return (sizeof(float) * stat_elems(p) + 255) / 256 * 256; }
 // compact copies of a branch's rows for the dK/dV kernel: Q, dO row-major, + 3 statistics
@@ -178,6 +191,21 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
             vt_glb = (char*)workspace + kv_copy_bytes(*p);
             if ((r = pack_kv(g, v_glb, vt_glb, kv_cap(*p), st)) != L2A_OK) return r;
         }
+    }
+    if (pair_fwd(*p)) {
+        char* after_v = (char*)workspace + 2 * kv_copy_bytes(*p);
+        float* A32 = (float*)(after_v + 2 * redo_bytes(*p));
+        // tokens the Global branch never visits
+        if (A_opt && (r = fill_zero(A_opt, q_elems(*p) * elem_bytes(*p), st)) != L2A_OK) return r;
+        if ((r = fill_f32(lse_global, stat_elems(*p), -INFINITY, st)) != L2A_OK) return r;
+        const RowSet rs_l{nullptr, nullptr, nullptr, 1};
+        const RowSet rs_g{row_idx, count, kblk_first_row, 0};
+        const FwdOut out_l{O, S_opt, lse_local, nullptr, nullptr, 0};
+        const FwdOut out_g{nullptr, A_opt, lse_global, nullptr, nullptr, 0, A32};
+        if ((r = mfma_fwd_pair(g, rs_l, q_loc, k_loc, v_loc, vt_loc, out_l, rs_g, q_glb, k_glb, v_glb, vt_glb, out_g,
+                               kv_cap(*p), (int32_t*)after_v, st)) != L2A_OK)
+            return r;
+        return merge_rows(g, rs_g, A32, O, st);
     }
     auto fwd_branch = [&](const RowSet& rs, const void* q, const void* k, const void* v, const void* vt,
                           const FwdOut& out) {

@@ -105,6 +105,23 @@ __global__ __launch_bounds__(kThreads) void pack_token_minor_kernel(PackArgs a) 
     }
 }
 
+// O = S + A on the rows of a set (Sec. 3.2 Eq. 5), for the forward that runs both branches in one
+// launch: O holds S, A the Global branch's rows in fp32, so that the sum is rounded once.  Sixteen
+// lanes per row, sixteen rows per workgroup.
+__global__ __launch_bounds__(kThreads) void merge_rows_kernel(Geom gm, RowSet rs, const float* __restrict__ A,
+                                                              __bf16* __restrict__ O) {
+    const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
+    const int r = blockIdx.x * (kThreads / 16) + (threadIdx.x >> 4);
+    if (r >= rows_total(rs, gm, bh)) return;
+    const int code = row_code(rs, gm, bh, r);
+    const int p = code / gm.G;
+    const int head = hk * gm.G + (code - p * gm.G);
+    const size_t off = (((size_t)b * gm.T + p) * gm.Hq + head) * kD + (threadIdx.x & 15) * 8;
+    const f32x8 x = *reinterpret_cast<const f32x8*>(A + off);
+    const bf16x8 y = *reinterpret_cast<const bf16x8*>(O + off);
+    *reinterpret_cast<bf16x8*>(O + off) = __builtin_convertvector(x + __builtin_convertvector(y, f32x8), bf16x8);
+}
+
 }  // namespace
 
 // rows = tokens of each KV head: x [B,T,Hkv,128] -> xt [B*Hkv][128][cap], cap = round_up(T, 64)
@@ -140,6 +157,15 @@ int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, co
     a.cap = cap;
     KernelTimer kt(rs.local ? "pack_rows_local" : "pack_rows_global", st);
     hipLaunchKernelGGL(pack_token_minor_kernel, dim3(cap / 64, g.B * g.Hkv), dim3(kThreads), 0, st, a);
+    return launch_status();
+}
+
+int merge_rows(const Geom& g, const RowSet& rs, const float* A, void* O, hipStream_t st) {
+    if (g.D != kD) return L2A_ERR_UNSUPPORTED;
+    const long long rows = (long long)g.T * g.G;
+    KernelTimer kt("merge_rows", st);
+    hipLaunchKernelGGL(merge_rows_kernel, dim3((unsigned)((rows + kThreads / 16 - 1) / (kThreads / 16)), g.B * g.Hkv),
+                       dim3(kThreads), 0, st, g, rs, A, (__bf16*)O);
     return launch_status();
 }
 

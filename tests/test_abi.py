@@ -51,6 +51,15 @@ def test_workspace_queries(lib):
     packed = 2 * (Bn * Hkv * cap * D * 2) + 3 * up(Bn * Hkv * cap * 4, 256)   # Q, dO rows + 3 statistics
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 0) == 2 * kv_copy + redo
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta + 2 * packed
+    # short sequences run both branches in one launch: the flags twice and a buffer for A in fp32
+    T = 4096
+    ps = B.make_params(1, T, 28, 4, 128, 4096, 1)
+    kv_copy_s = Bn * Hkv * D * up(T, 64) * 2
+    redo_s = up(4 * up(up(T * G, 256) // 256, 8) * Bn * Hkv, 256)
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(ps), 0) == 2 * kv_copy_s + 2 * redo_s + Bn * T * Hq * D * 4
+    for flag in (B.L2A_FLAG_SEQUENTIAL, B.L2A_FLAG_DENSE, B.L2A_FLAG_SKIP_GLOBAL, B.L2A_FLAG_SKIP_LOCAL):
+        ps.flags = flag
+        assert lib.l2a_attn_workspace_bytes(ctypes.byref(ps), 0) == 2 * kv_copy_s + redo_s
     p.flags = B.L2A_FLAG_SCALAR   # scalar kernels: only the two delta arrays
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 0) == 0
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta

@@ -175,11 +175,13 @@ def test_fp32_separate_branch_inputs(oracle):
 # ------------------------------------------------------------------------------------------
 # bf16 (matrix-core kernels)
 # ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("order", [0, B.L2A_FLAG_SEQUENTIAL])
 @pytest.mark.parametrize("Hm", ["shared", "q"])
-def test_bf16_layer_several_tiles_ragged(oracle, Hm):
+def test_bf16_layer_several_tiles_ragged(oracle, Hm, order):
+    """order: both branches in one launch (short sequences) / one after the other."""
     Hq, Hkv = 14, 2
     x = make_case(B_=1, T=1037, Hq=Hq, Hkv=Hkv, W=300, Hm=1 if Hm == "shared" else Hq, f=0.3, seed=6)
-    run_and_check(oracle, x)
+    run_and_check(oracle, x, flags=order)
 
 
 def test_bf16_batch_and_kv_mask(oracle):
@@ -195,6 +197,35 @@ def test_bf16_branch_flags(oracle):
     run_and_check(oracle, x, flags=B.L2A_FLAG_SKIP_LOCAL)
     run_and_check(oracle, x, flags=B.L2A_FLAG_SKIP_GLOBAL)
     run_and_check(oracle, x, flags=B.L2A_FLAG_SKIP_LOCAL | B.L2A_FLAG_DENSE)
+
+
+@pytest.mark.parametrize("order", [0, B.L2A_FLAG_SEQUENTIAL])
+def test_bf16_forward_without_branch_outputs(oracle, order):
+    """Inference: S_opt and A_opt are NULL; with both branches in one launch a then lives in the workspace."""
+    x = make_case(T=900, Hq=8, Hkv=2, W=100, f=0.4, seed=12)
+    ref = oracle.layer_fwd(oracle.Problem(x.q, x.k, x.v, x.mask, x.w.W))
+    lay = layer_from_numpy(x.q, x.k, x.v, x.mask, x.w.W, "bf16", order)
+    lay.route()
+    lay.forward(save_branches=False)
+    torch.cuda.synchronize()
+    assert_close("O", to_host(lay.O), ref["O"], "bf16")
+    assert_lse("lse_local", to_host(lay.lse_l), ref["lse_l"], "bf16")
+    assert_lse("lse_global", to_host(lay.lse_g), ref["lse_g"], "bf16")
+
+
+def test_bf16_one_launch_equals_sequential_bit_for_bit():
+    """Short sequences: both branches in one launch and o = s + d a formed afterwards from the fp32 a --
+    the same bits as the Global kernel adding its result to the stored s."""
+    x = make_case(T=2000, Hq=14, Hkv=2, W=300, Hm=14, f=0.3, seed=13)
+    outs = []
+    for order in (0, B.L2A_FLAG_SEQUENTIAL):
+        lay = layer_from_numpy(x.q, x.k, x.v, x.mask, x.w.W, "bf16", order)
+        lay.route()
+        lay.forward()
+        torch.cuda.synchronize()
+        outs.append({n: getattr(lay, n).clone() for n in ("O", "S", "A", "lse_l", "lse_g")})
+    for n in outs[0]:
+        assert torch.equal(outs[0][n], outs[1][n]), n
 
 
 def test_bf16_separate_branch_inputs(oracle):
@@ -242,26 +273,34 @@ def growing_scores_case(top, T=900, Hq=4, Hkv=2, W=200, seed=40):
 
 
 def redo_flags(lay):
-    """Flags of the tiles the pipelined forward kernel left to the fix-up kernel (last branch run):
-    they sit behind the two token-minor V copies in the forward workspace."""
+    """Flags of the tiles the pipelined forward kernel left to the fix-up kernel: they sit behind the two
+    token-minor V copies in the forward workspace -- those of the last branch run, or of both branches
+    when one launch carried both (short sequences without L2A_FLAG_SEQUENTIAL)."""
     p = lay.p
-    kv_copy = p.B * p.Hkv * p.D * ((p.T + 63) // 64 * 64) * 2
-    n = (p.T * (p.Hq // p.Hkv) + 255) // 256 * p.B * p.Hkv
-    return lay.fwd_ws[2 * kv_copy:2 * kv_copy + 4 * n].view(torch.int32).cpu().numpy()
+    up = lambda x, m: (x + m - 1) // m * m
+    kv_copy = p.B * p.Hkv * p.D * up(p.T, 64) * 2
+    n = up(up(p.T * (p.Hq // p.Hkv), 256) // 256, 8) * p.B * p.Hkv   # flags of one branch
+    both = lay.fwd_ws.numel() > 2 * kv_copy + up(4 * n, 256)
+    return lay.fwd_ws[2 * kv_copy:2 * kv_copy + (2 if both else 1) * 4 * n].view(torch.int32).cpu().numpy()
 
 
-def test_bf16_scores_above_reference_without_overflow(oracle):
+SEQ = [0, B.L2A_FLAG_SEQUENTIAL]   # short sequences: both branches in one launch / one after the other
+
+
+@pytest.mark.parametrize("order", SEQ)
+def test_bf16_scores_above_reference_without_overflow(oracle, order):
     """Scores exceed the fixed reference by up to e^40: sums stay in range, no tile is redone."""
-    lay, _ = run_and_check(oracle, growing_scores_case(40.0))
+    lay, _ = run_and_check(oracle, growing_scores_case(40.0), flags=order)
     assert not redo_flags(lay).any()
 
 
-def test_bf16_scores_overflow_reference_fixup_kernel(oracle):
+@pytest.mark.parametrize("order", SEQ)
+def test_bf16_scores_overflow_reference_fixup_kernel(oracle, order):
     """Scores exceed the reference by up to e^300: row sums overflow, the fix-up kernel takes over.
     Forward only: keys this large (|k| ~ 26 in every channel) multiply the rounding of the saved
     bf16 outputs, through delta = <dO, out>, into dQ = scale sum_j p (dp - delta) k_j beyond any
     fixed tolerance -- a property of bf16 storage of the outputs, not of the kernels."""
-    lay, _ = run_and_check(oracle, growing_scores_case(300.0), backward=False)
+    lay, _ = run_and_check(oracle, growing_scores_case(300.0), flags=order, backward=False)
     assert redo_flags(lay).any()
 
 
@@ -273,7 +312,8 @@ def test_bf16_scores_falling_along_sequence(oracle):
 @pytest.mark.parametrize("T,Hq,Hkv", [(129, 7, 1), (193, 3, 1), (2049, 2, 2), (4100, 14, 2), (300, 16, 1)])
 def test_bf16_ragged_tiles(oracle, T, Hq, Hkv):
     """Row counts and key counts just past tile boundaries; T * G not a multiple of the row tile."""
-    run_and_check(oracle, make_case(T=T, Hq=Hq, Hkv=Hkv, W=70, f=0.35, seed=50 + T % 13))
+    for order in (0, B.L2A_FLAG_SEQUENTIAL):
+        run_and_check(oracle, make_case(T=T, Hq=Hq, Hkv=Hkv, W=70, f=0.35, seed=50 + T % 13), flags=order)
 
 
 def _random_shape(i):
@@ -295,8 +335,9 @@ def _random_shape(i):
 def test_bf16_random_shapes(oracle, i):
     """Whole tensors, forward and backward, on shapes nobody picked by hand."""
     cfg = _random_shape(i)
-    print("case", cfg, flush=True)
-    run_and_check(oracle, make_case(**cfg))
+    order = B.L2A_FLAG_SEQUENTIAL if i % 2 else 0   # half of them with the branches one after the other
+    print("case", cfg, "flags", order, flush=True)
+    run_and_check(oracle, make_case(**cfg), flags=order)
 
 
 # ------------------------------------------------------------------------------------------
