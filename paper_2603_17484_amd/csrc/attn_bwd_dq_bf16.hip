@@ -61,23 +61,29 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
 
     const Geom& gm = a.gm;
     // Workgroups are dispatched in the order of their linear index and dealt round-robin to the 8 XCDs
-    // (the grid's width is a multiple of 8).  Global rows: longest prefixes first, over all (b, KV
-    // head) together -- with a few hundred tiles in all, a head whose long tiles started last would
-    // set the kernel's time; every tile starts at key block 0, so the tiles resident on an XCD read
-    // the same K/V blocks at about the same time whatever their order.  Local rows: each XCD takes
-    // a contiguous range of a head's tiles, so that the tiles resident on it have overlapping windows
-    // and share their K/V blocks through its L2 -- when the sequence is several windows long, so that
-    // the ranges cost the same; otherwise the tiles' costs grow with their position like the Global
-    // ones' and they are ordered the same way.
+    // (the grid's width is a multiple of 8).  Global rows: longest prefixes first; every tile starts
+    // at key block 0, so the tiles resident on an XCD read the same K/V blocks at about the same time
+    // whatever their order.  While the K and V of all heads together fit the last-level cache, the
+    // order runs over all (b, KV head) together (rotated, so that no XCD is tied to one head) -- with
+    // a few hundred tiles in all, a head whose long tiles started last would set the kernel's time;
+    // beyond that the heads go one after the other, so that the chip streams one head's K and V at a time.
+    // Local rows: each XCD takes a contiguous range of a head's tiles, so that the tiles resident on it
+    // have overlapping windows and share their K/V blocks through its L2 -- when the sequence is
+    // several windows long, so that the ranges cost the same; otherwise the tiles' costs grow with
+    // their position like the Global ones' and they are ordered the same way.
     int bh, rank;
     const bool by_range = LOCAL && gm.T / 4 > gm.W;
+    const int nbh = gridDim.y;
     if (by_range) {
         bh = blockIdx.y;
         rank = ((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3);
-    } else {
+    } else if ((long long)nbh * gm.T <= kAllHeadsMaxTokens) {
         const int lin = (int)(blockIdx.y * gridDim.x + blockIdx.x);
-        rank = lin / (int)gridDim.y;
-        bh = lin - rank * (int)gridDim.y;
+        rank = lin / nbh;
+        bh = (lin - rank * nbh + rank) % nbh;
+    } else {
+        bh = blockIdx.y;
+        rank = blockIdx.x;
     }
     const int b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
     const int n_rows = rows_total(a.rs, gm, bh);

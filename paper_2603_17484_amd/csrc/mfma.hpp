@@ -49,6 +49,10 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Tile orders of the forward and dQ kernels: tokens x (b, KV head) up to which the K and V of all
+// heads (512 bytes per token and head) are taken to fit the 256 MB last-level cache together
+constexpr long long kAllHeadsMaxTokens = 1 << 18;
+
 // index along the M dimension held by register r of a C/D tile
 __device__ __forceinline__ int c_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
