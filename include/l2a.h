@@ -86,7 +86,9 @@ const char* l2a_strerror(int code);
  *             l2a_attn_fwd) the flags twice and a [B,T,Hq,D] float buffer for a; else nothing
  *   backward  delta_t of each branch, [B,Hq,T] float, twice; on the matrix-core path also, per
  *             branch, compact row-major copies of the rows' Q and dO (ceil64(T G) rows per
- *             (b, KV head)) with three per-row statistics
+ *             (b, KV head)) with three per-row statistics; short sequences (fewer than 256
+ *             blocks of 128 keys over all (b, KV head)): up to 8 x 2 float copies of [B,T,Hkv,D],
+ *             partial sums of the workgroups that share a key block's rows
  */
 size_t l2a_route_workspace_bytes(const l2a_params* p);
 size_t l2a_attn_workspace_bytes(const l2a_params* p, int backward);

@@ -59,6 +59,8 @@ struct DkdvArgs {
     const __bf16* v;
     __bf16* dk;
     __bf16* dv;
+    int nsplit;             // workgroups per key block (grid.z): each takes a share of the row tiles
+    float* part;            // nsplit > 1: partial sums [nsplit][2][B, T, Hkv, D] instead of dk, dv
 };
 
 struct RowTileLds {
@@ -143,6 +145,13 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             if (r_suf < re) tl = min(tl, (int)(r_suf / kRT));
         }
         tt = max(tl, th);
+        if (a.nsplit > 1) {  // this workgroup's share of the tiles
+            const int nt = te - tb, z = blockIdx.z;
+            const int b2 = tb + (int)((long long)nt * z / a.nsplit), e2 = tb + (int)((long long)nt * (z + 1) / a.nsplit);
+            tb = b2, te = e2;
+            th = min(max(th, tb), te);
+            tt = min(max(tt, th), te);
+        }
     };
     int tb0, th0, tt0, te0, tb1, th1, tt1, te1;
     tile_runs(0, tb0, th0, tt0, te0);
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         const int nblk = (gm.T + kKeysPerWg - 1) / kKeysPerWg;
         const int last = min((kblk / a.chunk) * a.chunk + a.chunk - 1, nblk - 1);
         const int r = (int)(((long long)last * kKeysPerWg * gm.G) / kRT) - tb;
-        return r < n ? r : 0;  // ranges that do not overlap share nothing
+        return (r >= 0 && r < n) ? r : 0;  // ranges that do not overlap share nothing
     };
     const int rot0 = rotation(0, tb0, n0), rot1 = rotation(1, tb1, n1);
     // Loads walk the tiles with a cursor that is advanced once per step: tile te - 1 - j for a reversed
@@ -437,18 +446,48 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
             const int kk = kw0 + c_row(e, h);
             if (kk < gm.T) {
                 const size_t off = (((size_t)b * gm.T + kk) * gm.Hkv + hk) * kD + d * 32 + n;
-                a.dk[off] = (__bf16)(dkacc[d][e] * gm.scale);
-                a.dv[off] = (__bf16)dvacc[d][e];
+                if (a.nsplit > 1) {
+                    const size_t elems = (size_t)gm.B * gm.T * gm.Hkv * kD;
+                    float* pz = a.part + (size_t)blockIdx.z * 2 * elems;
+                    pz[off] = dkacc[d][e] * gm.scale;
+                    pz[elems + off] = dvacc[d][e];
+                } else {
+                    a.dk[off] = (__bf16)(dkacc[d][e] * gm.scale);
+                    a.dv[off] = (__bf16)dvacc[d][e];
+                }
             }
         }
 }
 
+// dk, dv = sum over the splits of their partial sums, rounded once
+__global__ __launch_bounds__(kThreads) void dkdv_reduce_kernel(const float* __restrict__ part, int nsplit, size_t elems,
+                                                               __bf16* __restrict__ dk, __bf16* __restrict__ dv) {
+    const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+    if (i >= elems) return;
+    __bf16* out = blockIdx.y ? dv : dk;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < nsplit; ++z)
+        acc += *reinterpret_cast<const f32x4*>(part + ((size_t)z * 2 + blockIdx.y) * elems + i);
+    *reinterpret_cast<bf16x4*>(out + i) = __builtin_convertvector(acc, bf16x4);
+}
+
 }  // namespace
+
+// Workgroups per key block: short sequences have too few key blocks to fill the chip (one workgroup
+// per compute unit); their row tiles are then shared out until there are two per compute unit.
+int dkdv_splits(const Geom& g) {
+    const long long nblk = (g.T + kKeysPerWg - 1) / kKeysPerWg;
+    int z = 1;
+    if (nblk * g.B * g.Hkv >= 256) return z;  // a workgroup per compute unit: splitting gains nothing (measured)
+    while (z < 8 && nblk * g.B * g.Hkv * z < 512) z *= 2;
+    return z;
+}
 
 // packed[s]: compact copies of set s made by pack_rows (5 pointers in the order of PackedRows).
 // With two sets every array of the second must lie the same number of bytes after the first's.
+// part: dkdv_splits(g) > 1: room for that many x 2 x (B T Hkv D) floats
 int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[5], int cap,
-                  const void* k, const void* v, void* dk, void* dv, hipStream_t st) {
+                  const void* k, const void* v, void* dk, void* dv, float* part, hipStream_t st) {
     if (g.D != kD) return L2A_ERR_UNSUPPORTED;
     DkdvArgs a{};
     a.gm = g;
@@ -469,9 +508,20 @@ int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* cons
     const int nblk = (g.T + kKeysPerWg - 1) / kKeysPerWg;
     a.chunk = std::max(1, std::min(32, nblk / 32));
     const int per = 8 * a.chunk;
-    const dim3 grid((nblk + per - 1) / per * per, g.B * g.Hkv);
-    KernelTimer kt("bwd_dkdv", st);
-    hipLaunchKernelGGL(bwd_dkdv_kernel, grid, dim3(kThreads), 0, st, a);
+    a.nsplit = dkdv_splits(g);
+    a.part = part;
+    if (a.nsplit > 1 && !part) return L2A_ERR_WORKSPACE;
+    const dim3 grid((nblk + per - 1) / per * per, g.B * g.Hkv, a.nsplit);
+    {
+        KernelTimer kt("bwd_dkdv", st);
+        hipLaunchKernelGGL(bwd_dkdv_kernel, grid, dim3(kThreads), 0, st, a);
+    }
+    if (a.nsplit > 1) {
+        const size_t elems = (size_t)g.B * g.T * g.Hkv * kD;
+        KernelTimer kt("dkdv_reduce", st);
+        hipLaunchKernelGGL(dkdv_reduce_kernel, dim3((unsigned)((elems / 4 + kThreads - 1) / kThreads), 2), dim3(kThreads), 0,
+                           st, part, a.nsplit, elems, a.dk, a.dv);
+    }
     return launch_status();
 }
 

@@ -106,7 +106,9 @@ int pack_rows(const Geom& g, const RowSet& rs, const void* q, const void* dO, co
 int mfma_bwd_dq(const Geom& g, const RowSet& rs, const void* q, const void* k, const void* v, const void* dO,
                 const float* lse, float* delta, void* dq, int accumulate, hipStream_t st);
 // packed[s]: the five outputs of pack_rows for set s (qc, gc, lse2_c, delta_c, pos_c)
+// part: scratch for dkdv_splits(g) x 2 x (B T Hkv D) floats when dkdv_splits(g) > 1 (short sequences)
+int dkdv_splits(const Geom& g);
 int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* const (*packed)[5], int cap,
-                  const void* k, const void* v, void* dk, void* dv, hipStream_t st);
+                  const void* k, const void* v, void* dk, void* dv, float* part, hipStream_t st);
 
 }  // namespace l2a

@@ -72,8 +72,13 @@ int rows_cap(const l2a_params& p) { return (int)(((long long)p.T * (p.Hq / p.Hkv
 size_t rows_copy_bytes(const l2a_params& p) { return (size_t)p.B * p.Hkv * rows_cap(p) * p.D * 2; }
 size_t rows_stat_bytes(const l2a_params& p) { return ((size_t)p.B * p.Hkv * rows_cap(p) * 4 + 255) / 256 * 256; }
 size_t packed_set_bytes(const l2a_params& p) { return 2 * rows_copy_bytes(p) + 3 * rows_stat_bytes(p); }
+// short sequences: partial dK, dV sums of the workgroups that share a key block
+size_t dkdv_part_bytes(const l2a_params& p) {
+    const int z = dkdv_splits(make_geom(p));
+    return z > 1 ? (size_t)z * 2 * p.B * p.T * p.Hkv * p.D * sizeof(float) : 0;
+}
 size_t bwd_workspace_bytes(const l2a_params& p) {
-    return 2 * delta_bytes(p) + (use_mfma(p) ? 2 * packed_set_bytes(p) : 0);
+    return 2 * delta_bytes(p) + (use_mfma(p) ? 2 * packed_set_bytes(p) + dkdv_part_bytes(p) : 0);
 }
 
 
@@ -307,7 +312,8 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
             if (rc2 != L2A_OK) return rc2;
             for (int j = 0; j < 5; ++j) packed[i][j] = out[j];
         }
-        return mfma_bwd_dkdv(g, sets, n, packed, cap, k, v, dk, dv, st);
+        float* part = dkdv_part_bytes(*p) ? (float*)(packed_base + 2 * packed_set_bytes(*p)) : nullptr;
+        return mfma_bwd_dkdv(g, sets, n, packed, cap, k, v, dk, dv, part, st);
     };
     if (out_alias) {
         const RowSet sets[2] = {rs_l, rs_g};

@@ -72,6 +72,8 @@ int row_deltas(const Geom& g, int dtype, const void* dO, const void* S, const vo
                float* delta_g, hipStream_t st) {
     int tok = 64;  // tokens per workgroup: as many as fit 64 KB of LDS with Hq heads
     while (tok > 1 && sizeof(float) * 2 * g.Hq * tok > 64 * 1024) tok /= 2;
+    // short sequences: fewer tokens per workgroup rather than a grid that leaves most of the chip idle
+    while (tok > 8 && (long long)((g.T + tok - 1) / tok) * g.B < 2048) tok /= 2;
     const size_t lds = sizeof(float) * 2 * g.Hq * tok;
     if (lds > 64 * 1024) return L2A_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)((g.T + tok - 1) / tok), (unsigned)g.B);

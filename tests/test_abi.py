@@ -57,6 +57,10 @@ def test_workspace_queries(lib):
     kv_copy_s = Bn * Hkv * D * up(T, 64) * 2
     redo_s = up(4 * up(up(T * G, 256) // 256, 8) * Bn * Hkv, 256)
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(ps), 0) == 2 * kv_copy_s + 2 * redo_s + Bn * T * Hq * D * 4
+    # ... and the backward shares each key block's row tiles between 4 workgroups (32 blocks x 4 heads x 4 = 512)
+    delta_s, cap_s = up(4 * Bn * Hq * T, 256), up(T * G, 64)
+    packed_s = 2 * (Bn * Hkv * cap_s * D * 2) + 3 * up(Bn * Hkv * cap_s * 4, 256)
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(ps), 1) == 2 * delta_s + 2 * packed_s + 4 * 2 * Bn * T * Hkv * D * 4
     for flag in (B.L2A_FLAG_SEQUENTIAL, B.L2A_FLAG_DENSE, B.L2A_FLAG_SKIP_GLOBAL, B.L2A_FLAG_SKIP_LOCAL):
         ps.flags = flag
         assert lib.l2a_attn_workspace_bytes(ctypes.byref(ps), 0) == 2 * kv_copy_s + redo_s
