@@ -56,8 +56,12 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     constexpr int kBQ = NW * kRW;            // rows per workgroup
     constexpr int kNL = 16 / NW;             // 16-byte loads a wavefront issues per K, V or K^T block
     constexpr int kLoadSlot0 = 23 - 2 * kNL;  // the loads of later blocks go out in the last slots of a block's first half
-    __shared__ __attribute__((aligned(1024))) __bf16 lds_k[3][kBK * 128];
-    __shared__ __attribute__((aligned(1024))) __bf16 lds_v[3][kBK * 128];
+    // K and V tiles in one array: a V tile lies a fixed 48 KB behind the K tile of the same buffer, so
+    // the reads of both share their per-lane addresses (the distance goes into the offset field)
+    __shared__ __attribute__((aligned(1024))) __bf16 lds_kv[2][3][kBK * 128];
+    auto& lds_k = lds_kv[0];
+    auto& lds_v = lds_kv[1];
+    constexpr int kVBehindK = 3 * kBK * 128;  // elements
 
     const Geom& gm = a.gm;
     // Workgroups are dispatched in the order of their linear index and dealt round-robin to the 8 XCDs
@@ -183,28 +187,22 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     // One half-block (32 keys k0..k0+31, half KB of its block): dS from `cur`, overlapped with S, dP
-    // of the next half-block into `nxt` (rows krow0.. of tiles kt_, vt_) and dQ += K^T dS (tile ktt).
-    auto half_block = [&](auto mask_tag, auto kb_tag, SdP& cur, SdP& nxt, const __bf16* kt_, const __bf16* vt_,
-                          int krow0, const __bf16* ktt, int k0, auto&& side) __attribute__((always_inline)) {
+    // of the next half-block into `nxt` (rows krow0.. of K tile kt_ and the V tile behind it) and dQ += K^T dS (this block's K tile through trp).
+    auto half_block = [&](auto mask_tag, auto kb_tag, SdP& cur, SdP& nxt, const __bf16* kt_,
+                          int krow0, const lds_cptr (&trp)[4][2], int k0, auto&& side) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         constexpr int KB = decltype(kb_tag)::value;
         const float c2 = gm.scale_log2;
         bf16x8 opnd[24 + kAhead];
         uint32_t dsw[2][4];  // dS as packed bf16 pairs: [16-key group][dword]
         float dsum = 0.f;
-        lds_cptr trp[4][2];  // this lane's pieces of the transposed reads in tile ktt
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            trp[d][0] = (lds_cptr)(uintptr_t)(lds_offset(ktt) + tr_off[d][0]);
-            trp[d][1] = (lds_cptr)(uintptr_t)(lds_offset(ktt) + tr_off[d][1]);
-        }
         // operand of slot m: m < 16 -> K (even) / V (odd) rows of the next half-block, ks = m / 2;
         // else this block's K read transposed: (16-key group, channel block)
         auto read_operand = [&](auto mc) {
             constexpr int mm = decltype(mc)::value;
             if constexpr (mm < 16) {
                 if constexpr ((mm & 1) == 0) opnd[mm] = rm_tr_row_operand(kt_, krow0 + n, mm >> 1, h);
-                else opnd[mm] = rm_tr_row_operand(vt_, krow0 + n, mm >> 1, h);
+                else opnd[mm] = rm_tr_row_operand(kt_ + kVBehindK, krow0 + n, mm >> 1, h);
             } else if constexpr (mm < 24) {  // this block's K tile read transposed: channel block, 16-key group
                 constexpr int d = (mm - 16) & 3;
                 opnd[mm] = rm_tr_col_operand_at(trp[d][0], trp[d][1], 2 * KB + ((mm - 16) >> 2), 0);
@@ -293,9 +291,15 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
             // half-block where the VALU has nothing to do.  Past the last block the last one is loaded again, into buffers nobody reads any more.
             const int jk = min(jb + 2, jb1);
             {  // wavefronts whose rows all lie past the end compute on a repeated row and store nothing
-                const __bf16* ktt = &lds_k[buf][0];  // this block's K, read transposed for dQ += dS K
+                // this block's K, read transposed for dQ += dS K: this lane's pieces of the reads, for both half-blocks
+                lds_cptr trp[4][2];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    trp[d][0] = (lds_cptr)(uintptr_t)(lds_offset(&lds_k[buf][0]) + tr_off[d][0]);
+                    trp[d][1] = (lds_cptr)(uintptr_t)(lds_offset(&lds_k[buf][0]) + tr_off[d][1]);
+                }
                 BlockLoads L;
-                half_block(mask_tag, Int<0>{}, Xa, Xb, &lds_k[buf][0], &lds_v[buf][0], 32, ktt, jb * kBK, [&](auto mc) {
+                half_block(mask_tag, Int<0>{}, Xa, Xb, &lds_k[buf][0], 32, trp, jb * kBK, [&](auto mc) {
                     constexpr int mm = decltype(mc)::value;
                     if constexpr (mm == kLoadSlot0 - 1) {
                         const size_t src = (size_t)jk * kBK * kv_row_bytes;
@@ -307,7 +311,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
                     }
                     if constexpr (mm >= kLoadSlot0 && mm < kLoadSlot0 + 2 * kNL) issue_block_load(L, Int<mm - kLoadSlot0>{});
                 });
-                half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], &lds_v[buf1][0], 0, ktt, jb * kBK + 32,
+                half_block(mask_tag, Int<1>{}, Xb, Xa, &lds_k[buf1][0], 0, trp, jb * kBK + 32,
                            [](auto) {});
             }
             dma_wait();
