@@ -27,10 +27,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 # dispatch) scaled by what the same counters read for a plain 1 GiB device copy (--calibrate-copy):
 # FETCH x 2.0, WRITE x 1.0.  The counters cannot be read from inside the process, so the figures of the
 # committed profile are repeated here; they are reported only for exactly that workload.
-MEASURED_TRAFFIC_BYTES = {
-    "bwd_dkdv": 1.851e10, "bwd_dq_global": 1.769e10, "bwd_dq_local": 4.26e9,
-    "fwd_global": 1.484e10, "fwd_local": 5.24e9,
-}
+MEASURED_TRAFFIC_BYTES = {"bwd_dkdv": 1.700e10, "bwd_dq_global": 1.746e10, "bwd_dq_local": 4.25e9,
+                          "fwd_global": 1.487e10, "fwd_local": 5.40e9}
 
 
 def pair_counts(mask: np.ndarray, Hq: int, Hkv: int, T: int, W: int, dense: bool):
