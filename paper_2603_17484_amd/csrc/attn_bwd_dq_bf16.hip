@@ -67,7 +67,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_kernel(DqArgs a) {
     // Workgroups are dispatched in the order of their linear index and dealt round-robin to the 8 XCDs
     // (the grid's width is a multiple of 8).  Global rows: longest prefixes first; every tile starts
     // at key block 0, so the tiles resident on an XCD read the same K/V blocks at about the same time
-    // whatever their order.  While the K and V of all heads together fit the last-level cache, the
+    // whatever their order.  While the K and V of all heads together about fit the last-level cache, the
     // order runs over all (b, KV head) together (rotated, so that no XCD is tied to one head) -- with
     // a few hundred tiles in all, a head whose long tiles started last would set the kernel's time;
     // beyond that the heads go one after the other, so that the chip streams one head's K and V at a time.
