@@ -46,7 +46,7 @@ struct FwdArgs {
     const __bf16* v;   // V as given (fix-up kernel only)
     const __bf16* vt;  // token-minor copy of V: [B*Hkv][128][vt_cap]
     int vt_cap;
-    int32_t* redo;  // [B*Hkv][gridDim.x]: set to 1 for a tile whose rows must be recomputed by the fix-up kernel
+    int32_t* redo;  // [B*Hkv][width of the branch's grid]: set to 1 for a tile whose rows must be recomputed by the fix-up kernel
     FwdOut out;
 };
 
