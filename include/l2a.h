@@ -79,7 +79,7 @@ const char* l2a_strerror(int code);
  * Host-only, pure: scratch bytes each call needs (0 is possible; then workspace may be NULL).
  * The workspace is device memory owned by the caller, 256-byte aligned, not preserved between
  * calls; calls that share one workspace must be ordered on one stream.  What it holds:
- *   route     one int32 count per (b, mask head, 2048-position chunk)
+ *   route     one int32 count per (b, KV head, chunk of 2048 positions; of 256 for T <= 16384)
  *   forward   bf16, D = 128 without L2A_FLAG_SCALAR: a token-minor copy [B,Hkv,D,ceil64(T)] of
  *             each branch's V and one int32 flag per tile of 256 rows (tiles per (b, KV head)
  *             rounded up to a multiple of 8); when both branches run in one launch (see

@@ -14,7 +14,9 @@ namespace l2a {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kChunk = 2048;  // positions per workgroup
+// positions per workgroup: 2048, or 256 for sequences so short that 2048 would leave a handful of
+// workgroups walking their chunks step by step
+__host__ __device__ inline int chunk_positions(int T) { return T <= 16384 ? 256 : 2048; }
 constexpr int kMaxG = 16;
 
 struct RouteArgs {
@@ -23,7 +25,7 @@ struct RouteArgs {
     int32_t* count;
     int32_t* kblk_first_row;
     int32_t* chunk_cnt;
-    int B, T, Hq, Hkv, G, Hm, nchunks, nkb;
+    int B, T, Hq, Hkv, G, Hm, nchunks, nkb, chunk;
 };
 
 // mask row of query head (hk, g)
@@ -51,8 +53,8 @@ __global__ __launch_bounds__(kThreads) void route_count_kernel(RouteArgs a) {
     int n = 0;
     for (int g = 0; g < gdistinct; ++g) {
         const uint8_t* m = mask_row(a, b, hk, g);
-        for (int i = threadIdx.x; i < kChunk; i += kThreads) {
-            const int pos = chunk * kChunk + i;
+        for (int i = threadIdx.x; i < a.chunk; i += kThreads) {
+            const int pos = chunk * a.chunk + i;
             if (pos < a.T && m[pos] != 0) n += weight;
         }
     }
@@ -87,8 +89,8 @@ __global__ __launch_bounds__(kThreads) void route_write_kernel(RouteArgs a) {
 
     const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));  // lanes below this one
     int running = before;
-    for (int step = 0; step < kChunk / kThreads; ++step) {
-        const int pos = chunk * kChunk + step * kThreads + threadIdx.x;
+    for (int step = 0; step < a.chunk / kThreads; ++step) {
+        const int pos = chunk * a.chunk + step * kThreads + threadIdx.x;
         // bit g of `bits` = d(b, hk*G+g, pos)
         unsigned bits = 0;
         if (pos < a.T) {
@@ -123,9 +125,9 @@ __global__ __launch_bounds__(kThreads) void route_write_kernel(RouteArgs a) {
         running += stot;
     }
 
-    // unused tail: this workgroup owns slots [chunk*kChunk*G, (chunk+1)*kChunk*G)
-    const long long lo = (long long)chunk * kChunk * G;
-    long long hi = lo + (long long)kChunk * G;
+    // unused tail: this workgroup owns slots [chunk * a.chunk * G, (chunk + 1) * a.chunk * G)
+    const long long lo = (long long)chunk * a.chunk * G;
+    long long hi = lo + (long long)a.chunk * G;
     const long long cap = (long long)a.T * G;
     if (hi > cap) hi = cap;
     for (long long s = lo + threadIdx.x; s < hi; s += kThreads)
@@ -135,7 +137,8 @@ __global__ __launch_bounds__(kThreads) void route_write_kernel(RouteArgs a) {
 }  // namespace
 
 size_t route_workspace_bytes(const l2a_params& p) {
-    const size_t nchunks = ((size_t)p.T + kChunk - 1) / kChunk;
+    const size_t chunk = chunk_positions(p.T);
+    const size_t nchunks = ((size_t)p.T + chunk - 1) / chunk;
     return sizeof(int32_t) * nchunks * (size_t)p.B * (size_t)p.Hkv;
 }
 
@@ -148,7 +151,8 @@ int route_compact(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, in
     a.kblk_first_row = kblk_first_row;
     a.chunk_cnt = (int32_t*)ws;
     a.B = p.B; a.T = p.T; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = p.Hq / p.Hkv; a.Hm = p.mask_heads;
-    a.nchunks = (p.T + kChunk - 1) / kChunk;
+    a.chunk = chunk_positions(p.T);
+    a.nchunks = (p.T + a.chunk - 1) / a.chunk;
     a.nkb = (p.T + 63) / 64;
     if (a.G > kMaxG) return L2A_ERR_UNSUPPORTED;
     const dim3 grid(a.nchunks, p.B * p.Hkv);

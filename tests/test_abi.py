@@ -69,6 +69,7 @@ def test_workspace_queries(lib):
     assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * delta
     p.flags = 0
     assert lib.l2a_route_workspace_bytes(ctypes.byref(p)) == 4 * 4 * (131072 // 2048)
+    assert lib.l2a_route_workspace_bytes(ctypes.byref(B.make_params(2, 5000, 28, 4, 128, 4096, 1))) == 4 * 2 * 4 * 20  # chunks of 256
     assert lib.l2a_kblk_entries(131072) == 2049 and lib.l2a_kblk_entries(65) == 3
     p.flags = B.L2A_FLAG_DENSE
     assert lib.l2a_route_workspace_bytes(ctypes.byref(p)) == 0
