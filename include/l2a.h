@@ -172,7 +172,8 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
  *
  *   p->T        capacity of the cache in tokens (the row stride of k_cache / v_cache)
  *   q           in  [B,Hq,D]      the new token's queries
- *   k_cache,v_cache  in  [B,T,Hkv,D]  rows 0..pos[b] valid (the new token's own K, V included)
+ *   k_cache,v_cache  in  [B,T,Hkv,D]  rows 0..pos[b] valid (the new token's own K, V included); what
+ *                   the rows behind pos[b] hold never enters the result
  *   pos         in  [B] int32, device memory: position of the new token, 0 <= pos[b] < T
  *                   (device data cannot be validated on the host: values outside are clamped into the range)
  *   mask        in  [B,mask_heads] uint8, device memory: the new token's decisions

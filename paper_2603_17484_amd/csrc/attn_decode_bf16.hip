@@ -95,12 +95,14 @@ __global__ __launch_bounds__(64 * kWaves) void decode_partial_kernel(DecodeArgs 
     auto load = [&](int sb, int buf) __attribute__((always_inline)) {
         const size_t src = (size_t)sb * kSub * kv_row_bytes;
         const unsigned dst = lds0 + buf * (unsigned)sizeof(lds[0][0]);
-        if ((sb + 1) * kSub <= gm.T) {
+        if ((sb + 1) * kSub <= hi + 1) {
             rm_dma_issue(off, kbase + src, dst, 0);
             rm_dma_issue(off_tr, vbase + src, dst + kSub * 256, 0);
-        } else {  // ragged end of the cache: rows past it repeat the last one (always masked)
-            rm_dma_issue_clamped<kSub, 1>(kv_row_bytes, gm.T - sb * kSub, kbase + src, dst, 0);
-            const int valid = gm.T - sb * kSub;
+        } else {  // the sub-block that holds the new token: the rows behind it are not written yet (or past
+                  // the end of the cache) and may hold anything, NaN patterns included, which a zero
+                  // weight would not keep out of the sums: they repeat the last valid row (always masked)
+            rm_dma_issue_clamped<kSub, 1>(kv_row_bytes, hi + 1 - sb * kSub, kbase + src, dst, 0);
+            const int valid = hi + 1 - sb * kSub;
 #pragma unroll
             for (int i = 0; i < kSub / 4; ++i) {
                 const int row = i * 4 + (lane >> 4);

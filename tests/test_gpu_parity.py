@@ -525,7 +525,7 @@ def test_router_decide(oracle, dtype, C, T, tau):
 # ------------------------------------------------------------------------------------------
 # decode step (Sec. 3.4): one new token per sequence against the KV cache
 # ------------------------------------------------------------------------------------------
-def decode_case(oracle, Bn, Tcap, Hq, Hkv, W, pos, Hm, f, seed, flags=0, pos_given=None):
+def decode_case(oracle, Bn, Tcap, Hq, Hkv, W, pos, Hm, f, seed, flags=0, pos_given=None, poison=False):
     """The oracle is the layer's definition at row t = pos[b]: whatever the cache holds beyond pos is
     out of reach of a causal row, so the same K/V arrays serve as the cache."""
     rng = np.random.default_rng(seed)
@@ -550,7 +550,12 @@ def decode_case(oracle, Bn, Tcap, Hq, Hkv, W, pos, Hm, f, seed, flags=0, pos_giv
     out = {n: torch.full((Bn, Hq, D), 7.0, dtype=torch.bfloat16, device="cuda") for n in ("O", "S", "A")}
     lse_l = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
     lse_g = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
-    B.l2a_attn_decode(p, to_device(qn, "bf16"), to_device(k, "bf16"), to_device(v, "bf16"),
+    kd, vd = to_device(k, "bf16"), to_device(v, "bf16")
+    if poison:   # cache rows behind the new token are not written yet: they may hold anything
+        for b in range(Bn):
+            kd[b, pos[b] + 1:] = float("nan")
+            vd[b, pos[b] + 1:] = float("nan")
+    B.l2a_attn_decode(p, to_device(qn, "bf16"), kd, vd,
                       torch.from_numpy(pos if pos_given is None else np.asarray(pos_given, dtype=np.int32)).cuda(),
                       None if dense else torch.from_numpy(d).cuda(), out["O"], lse_l, lse_g,
                       out["S"], out["A"])
@@ -599,9 +604,16 @@ def test_decode_positions_outside_the_cache_are_clamped(oracle):
                 pos_given=[777, -5, 2 ** 31 - 1])
 
 
+@pytest.mark.parametrize("pos", [[0, 5], [31, 32], [100, 513], [1022, 700]])
+def test_decode_rows_behind_the_new_token_are_never_used(oracle, pos):
+    """NaN in every cache row after pos: a zero weight would not keep it out of the sums."""
+    decode_case(oracle, 2, 1024, 8, 2, 300, pos, 8, 0.6, seed=95, poison=True)
+
+
 @pytest.mark.timeout(600)
 def test_decode_full_length_cache(oracle):
-    """Qwen2.5-7B head layout, 128K cache, a routed and an unrouted sequence."""
+    """Qwen2.5-7B head layout, 128K cache, a routed and an unrouted sequence; the cache rows behind
+    each new token hold NaN."""
     rng = np.random.default_rng(5)
     Bn, T, Hq, Hkv, D, W = 2, 131072, 28, 4, 128, 4096
     k = gen.normal_tensor((Bn, T, Hkv, D), 5, 1, "bf16")
@@ -620,7 +632,11 @@ def test_decode_full_length_cache(oracle):
     p = B.make_params(Bn, T, Hq, Hkv, D, W, 1)
     O = torch.empty((Bn, Hq, D), dtype=torch.bfloat16, device="cuda")
     lse_g = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
-    B.l2a_attn_decode(p, to_device(qn, "bf16"), to_device(k, "bf16"), to_device(v, "bf16"), torch.from_numpy(pos).cuda(),
+    kd, vd = to_device(k, "bf16"), to_device(v, "bf16")
+    for b in range(Bn):
+        kd[b, pos[b] + 1:] = float("nan")
+        vd[b, pos[b] + 1:] = float("nan")
+    B.l2a_attn_decode(p, to_device(qn, "bf16"), kd, vd, torch.from_numpy(pos).cuda(),
                       torch.from_numpy(d).cuda(), O, None, lse_g)
     torch.cuda.synchronize()
     assert_close("O", to_host(O), (ref["S"] + ref["A"]).reshape(Bn, Hq, D), "bf16")
