@@ -228,6 +228,29 @@ def test_bf16_one_launch_equals_sequential_bit_for_bit():
         assert torch.equal(outs[0][n], outs[1][n]), n
 
 
+@pytest.mark.parametrize("order", [0, B.L2A_FLAG_SEQUENTIAL])
+def test_bf16_workspaces_may_hold_anything(order):
+    """The workspaces are scratch: filled with 0xFF bytes (NaN patterns, negative integers) before
+    the calls, they must give the same bits as before."""
+    x = make_case(T=1100, Hq=14, Hkv=2, W=200, Hm=14, f=0.3, seed=14)
+    lay = layer_from_numpy(x.q, x.k, x.v, x.mask, x.w.W, "bf16", order)
+    dO = to_device(x.dO, "bf16")
+    names = ("O", "S", "A", "lse_l", "lse_g", "dq", "dk", "dv")
+
+    def step():
+        lay.route(); lay.forward(); lay.backward(dO)
+        torch.cuda.synchronize()
+        return {n: getattr(lay, n).clone() for n in names}
+
+    first = step()
+    for ws in (lay.route_ws, lay.fwd_ws, lay.bwd_ws):
+        ws.view(torch.uint8).fill_(0xFF)
+    second = step()
+    for n in names:
+        assert not torch.isnan(second[n].float()).any(), n
+        assert torch.equal(first[n], second[n]), n
+
+
 def test_bf16_separate_branch_inputs(oracle):
     run_and_check(oracle, make_case(T=390, Hq=4, Hkv=2, W=33, f=0.4, seed=10), separate=True)
 
