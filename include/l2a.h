@@ -48,6 +48,7 @@ enum {
     L2A_FLAG_SKIP_GLOBAL = 4, /* run the Local branch only:   O = s    */
     L2A_FLAG_SEQUENTIAL = 8,  /* forward: run the branches one after the other at every length (see
                                  l2a_attn_fwd: short sequences otherwise run them in one launch) */
+    L2A_FLAG_RING_CACHE = 16, /* l2a_attn_decode with L2A_FLAG_SKIP_GLOBAL: the cache is a ring (see there) */
     L2A_FLAG_SCALAR = 1 << 16 /* bf16 only: use the scalar-FMA kernels instead of the matrix-core ones
                                  (slow; for cross-checking) */
 };
@@ -182,6 +183,12 @@ int l2a_attn_fwd(const l2a_params* p, const void* q_loc, const void* k_loc, cons
  *   lse_local, lse_global  out optional [B,Hq]; lse_global is -inf where d = 0
  *   S_opt, A_opt  out optional [B,Hq,D]; A is zero where d = 0
  *   workspace   l2a_decode_workspace_bytes(p): one partial (max, sum, O) per 512 keys, head and branch
+ *
+ * L2A_FLAG_RING_CACHE (with L2A_FLAG_SKIP_GLOBAL; a Local module of its own keeps only its window):
+ * the cache is a ring of p->T >= W + 1 slots (a multiple of 32), the K, V of token j in slot j mod p->T, and pos[b] is the
+ * new token's position in the sequence, however long (negative values are clamped to 0).  Slots not
+ * yet written (pos[b] < p->T - 1) are never used.  Errors: L2A_ERR_UNSUPPORTED without
+ * L2A_FLAG_SKIP_GLOBAL, with p->T < W + 1 or p->T not a multiple of 32.
  */
 size_t l2a_decode_workspace_bytes(const l2a_params* p);
 int l2a_attn_decode(const l2a_params* p, const void* q, const void* k_cache, const void* v_cache,

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libl2a.so")
 L2A_BF16, L2A_FP32 = 0, 1
 L2A_FLAG_DENSE, L2A_FLAG_SKIP_LOCAL, L2A_FLAG_SKIP_GLOBAL = 1, 2, 4
 L2A_FLAG_SEQUENTIAL = 8
+L2A_FLAG_RING_CACHE = 16
 L2A_FLAG_SCALAR = 1 << 16
 
 EXPORTS = ("l2a_version", "l2a_strerror", "l2a_route_workspace_bytes", "l2a_attn_workspace_bytes",

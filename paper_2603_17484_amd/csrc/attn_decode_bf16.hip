@@ -38,6 +38,7 @@ struct DecodeArgs {
     const uint8_t* mask;  // [B, mask_heads]; nullptr: every head routed
     int mask_heads;
     int do_local, do_global;
+    int ring;           // the cache is a ring of gm.T slots: key j lies in slot j mod gm.T, pos is unbounded (Local only)
     float* part;        // [B*Hq][2][nchunks][kPart]
     int nchunks;        // chunks per sequence, = ceil(T / chunk)
     int chunk;
@@ -54,6 +55,7 @@ __device__ __forceinline__ bool head_routed(const DecodeArgs& a, int b, int head
     return a.mask[(size_t)b * a.mask_heads + mh] != 0;
 }
 
+template <bool RING>
 __global__ __launch_bounds__(64 * kWaves) void decode_partial_kernel(DecodeArgs a) {
     // per wavefront: kBufs buffers of (K tile, V tile), 32 keys x 128 channels each
     __shared__ __attribute__((aligned(1024))) __bf16 lds[kWaves][kBufs][2][kSub * 128];
@@ -65,17 +67,28 @@ __global__ __launch_bounds__(64 * kWaves) void decode_partial_kernel(DecodeArgs 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, h = lane >> 5;
 
-    const int t = min(max(a.pos[b], 0), gm.T - 1);  // positions outside the cache are clamped, never followed
+    // positions outside the cache are clamped, never followed; in a ring only negative ones are
+    const int t_abs = max(a.pos[b], 0);
+    const int t = min(t_abs, gm.T - 1);
     if (branch == 0 ? !a.do_local : !a.do_global) return;
     if (branch == 1) {  // Global attention is skipped entirely when no head of the group is routed
         bool any = false;
         for (int g = 0; g < gm.G; ++g) any = any || head_routed(a, b, hk * gm.G + g);
         if (!any) return;
     }
-    const int lo = branch == 0 ? max(t - gm.W, 0) : 0, hi = t;  // keys lo..hi
+    // keys lo..hi; in a ring: slots 0..hi are written, which of them lie in the window is decided per key
+    const int lo = (branch == 0 && !RING) ? max(t - gm.W, 0) : 0, hi = t;
     const int c0 = chunk * a.chunk;
     if (c0 > hi || c0 + a.chunk <= lo) return;
     const int kb = max(c0, lo) / kSub, ke = min(c0 + a.chunk - 1, hi) / kSub;  // sub-blocks kb..ke of this chunk
+    // Which keys of a sub-block count is decided without branches (a basic-block boundary between
+    // the score instructions and the code that reads their results costs the compiler its
+    // bookkeeping of the wait between them).  Without a ring: lo <= key <= hi.  In a ring the token
+    // in slot `key` is age = (t_ref - key) mod T positions back and counts if age <= W; a ring that
+    // has not wrapped yet (t_abs < T) must not wrap either: its slots behind the new token are
+    // unwritten.  (A wrapped ring has a multiple of 32 slots, so no sub-block reaches past its end.)
+    const unsigned t_ref = RING ? t_abs % gm.T : 0;
+    const unsigned wrap = (RING && t_abs >= gm.T) ? gm.T : 0;
 
     // Q of the group's heads as B operands: lane n = row (head in group), rows >= G repeat the last head
     const int head = hk * gm.G + min(n, gm.G - 1);
@@ -144,21 +157,32 @@ __global__ __launch_bounds__(64 * kWaves) void decode_partial_kernel(DecodeArgs 
         // streaming softmax, one row per lane (the lane 32 apart holds the row's other 16 keys)
         const int k0 = sb * kSub;
         float mx = -INFINITY;
+        const int lo_l = lo - k0 - 4 * h, hi_l = hi - k0 - 4 * h;  // the lane's keys are k0 + 4 h + cr
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int key = k0 + c_row(r, h);
-            s[r] = (key >= lo && key <= hi) ? s[r] * gm.scale_log2 : -INFINITY;
+            const int cr = 8 * (r >> 2) + (r & 3);
+            bool ok;
+            if constexpr (RING) {
+                const unsigned d = t_ref - (unsigned)(k0 + 4 * h + cr), age = min(d, d + wrap);  // d < 0 reads as a huge number
+                ok = age <= (unsigned)gm.W;
+            } else {
+                ok = cr >= lo_l && cr <= hi_l;
+            }
+            s[r] = ok ? s[r] * gm.scale_log2 : -INFINITY;
             mx = fmaxf(mx, s[r]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float mnew = fmaxf(m, mx);  // every sub-block of the range has a valid key: mnew is finite
-        const float alpha = fast_exp2(m - mnew);  // exp2(-inf) = 0 on the first step
+        // a ring larger than the window has sub-blocks out of reach: while no key has been seen the
+        // running maximum stays -inf and the exponentials take 0 as their reference (all of them are 0)
+        const float mnew = fmaxf(m, mx);  // without a ring every sub-block of the range has a valid key: mnew is finite
+        const float mref = (RING && mnew == -INFINITY) ? 0.f : mnew;
+        const float alpha = fast_exp2(m - mref);  // exp2(-inf) = 0 on the first step
         m = mnew;
         float rsum = 0.f;
         uint32_t pw[2][4];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-            const float p0 = fast_exp2(s[r] - mnew), p1 = fast_exp2(s[r + 1] - mnew);
+            const float p0 = fast_exp2(s[r] - mref), p1 = fast_exp2(s[r + 1] - mref);
             rsum += p0 + p1;
             f32x2 f = {p0, p1};
             pw[r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
@@ -226,13 +250,13 @@ __global__ __launch_bounds__(kSlices * kD) void decode_combine_kernel(DecodeArgs
     const Geom& gm = a.gm;
     const int bhq = blockIdx.x, b = bhq / gm.Hq, head = bhq - b * gm.Hq;
     const int c = threadIdx.x & (kD - 1), slice = threadIdx.x >> 7;
-    const int t = min(max(a.pos[b], 0), gm.T - 1);
+    const int t = min(max(a.pos[b], 0), gm.T - 1);  // ring: the last written slot while it fills up, then the last slot
     float out[2] = {0.f, 0.f};
     float lse[2] = {-INFINITY, -INFINITY};
     for (int branch = 0; branch < 2; ++branch) {
         const bool on = branch == 0 ? a.do_local != 0 : (a.do_global && head_routed(a, b, head));
         if (!on) continue;  // uniform over the workgroup
-        const int lo = branch == 0 ? max(t - gm.W, 0) : 0;
+        const int lo = (branch == 0 && !a.ring) ? max(t - gm.W, 0) : 0;
         const int c_lo = lo / a.chunk, c_hi = t / a.chunk;
         const float* base = a.part + (((size_t)bhq * 2 + branch) * a.nchunks) * kPart;
         float mm = -INFINITY, ll = 0.f, oo = 0.f;
@@ -241,7 +265,10 @@ __global__ __launch_bounds__(kSlices * kD) void decode_combine_kernel(DecodeArgs
             const float* src = base + (size_t)ch * kPart;
             const float m1 = src[0], l1 = src[1], o1 = src[4 + c];
             const float mn = fmaxf(mm, m1);
-            const float s0 = fast_exp2(mm - mn), s1 = fast_exp2(m1 - mn);  // exp2(-inf) = 0 on the first chunk
+            // exp2(-inf) = 0 on the first chunk; a chunk of a ring may have no slot in the window (m1 = -inf):
+            // while nothing has been seen the reference is 0 and both factors are 0
+            const float mref = mn == -INFINITY ? 0.f : mn;
+            const float s0 = fast_exp2(mm - mref), s1 = fast_exp2(m1 - mref);
             ll = ll * s0 + l1 * s1;
             oo = oo * s0 + o1 * s1;
             mm = mn;
@@ -281,7 +308,7 @@ size_t decode_partial_floats(const Geom& g) {
 }
 
 int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, const int32_t* pos, const uint8_t* mask,
-                int mask_heads, int do_local, int do_global, float* part, void* O, void* S, void* A, float* lse_l,
+                int mask_heads, int do_local, int do_global, int ring, float* part, void* O, void* S, void* A, float* lse_l,
                 float* lse_g, hipStream_t st) {
     if (g.D != kD || g.G > 16) return L2A_ERR_UNSUPPORTED;  // the merge stage holds kWaves x G partials in LDS
     DecodeArgs a{};
@@ -294,6 +321,7 @@ int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, cons
     a.mask_heads = mask_heads;
     a.do_local = do_local;
     a.do_global = do_global;
+    a.ring = ring;
     a.part = part;
     a.chunk = kChunk;
     a.nchunks = (g.T + a.chunk - 1) / a.chunk;
@@ -304,7 +332,10 @@ int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, cons
     a.lse_g = lse_g;
     {
         KernelTimer kt("decode_partial", st);
-        hipLaunchKernelGGL(decode_partial_kernel, dim3(a.nchunks, 2, g.B * g.Hkv), dim3(64 * kWaves), 0, st, a);
+        if (ring)
+            hipLaunchKernelGGL(decode_partial_kernel<true>, dim3(a.nchunks, 2, g.B * g.Hkv), dim3(64 * kWaves), 0, st, a);
+        else
+            hipLaunchKernelGGL(decode_partial_kernel<false>, dim3(a.nchunks, 2, g.B * g.Hkv), dim3(64 * kWaves), 0, st, a);
     }
     {
         KernelTimer kt("decode_combine", st);

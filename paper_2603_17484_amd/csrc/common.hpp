@@ -94,7 +94,7 @@ int mfma_fwd_pair(const Geom& g, const RowSet& rs_l, const void* q_l, const void
 // ---- attn_decode_bf16.hip : one new token per sequence against the KV cache (bf16, D = 128)
 size_t decode_partial_floats(const Geom& g);
 int mfma_decode(const Geom& g, const void* q, const void* k, const void* v, const int32_t* pos, const uint8_t* mask,
-                int mask_heads, int do_local, int do_global, float* part, void* O, void* S, void* A, float* lse_l,
+                int mask_heads, int do_local, int do_global, int ring, float* part, void* O, void* S, void* A, float* lse_l,
                 float* lse_g, hipStream_t st);
 
 // ---- pack.hip : layout pre-passes (token-minor copies for the matrix-core kernels)

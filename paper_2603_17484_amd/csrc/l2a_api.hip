@@ -156,8 +156,11 @@ int l2a_attn_decode(const l2a_params* p, const void* q, const void* k_cache, con
         if (x && misaligned(x)) return L2A_ERR_ALIGN;
     if (!workspace || workspace_bytes < l2a_decode_workspace_bytes(p)) return L2A_ERR_WORKSPACE;
     if (misaligned(workspace)) return L2A_ERR_ALIGN;
+    const int ring = (p->flags & L2A_FLAG_RING_CACHE) ? 1 : 0;
+    // a ring serves the Local branch alone, must hold the whole window, and is walked in whole sub-blocks of 32 slots
+    if (ring && (!(p->flags & L2A_FLAG_SKIP_GLOBAL) || p->T < p->W + 1 || p->T % 32 != 0)) return L2A_ERR_UNSUPPORTED;
     return mfma_decode(make_geom(*p), q, k_cache, v_cache, pos, dense ? nullptr : mask, p->mask_heads,
-                       !(p->flags & L2A_FLAG_SKIP_LOCAL), !(p->flags & L2A_FLAG_SKIP_GLOBAL), (float*)workspace, O,
+                       !(p->flags & L2A_FLAG_SKIP_LOCAL), !(p->flags & L2A_FLAG_SKIP_GLOBAL), ring, (float*)workspace, O,
                        S_opt, A_opt, lse_local, lse_global, (hipStream_t)stream);
 }
 

@@ -147,3 +147,8 @@ def test_decode_argument_errors_and_workspace(lib):
     assert call(q=ctypes.c_void_p(0x1008)) == -5
     pf = B.make_params(2, 5000, 28, 4, 128, 4096, 1, B.L2A_FP32)
     assert call(pp=pf) == -3 and lib.l2a_decode_workspace_bytes(ctypes.byref(pf)) == 0
+    # a ring cache serves the Local branch alone and must hold the whole window
+    assert call(pp=B.make_params(2, 5000, 28, 4, 128, 4096, 1, B.L2A_BF16, B.L2A_FLAG_RING_CACHE)) == -3
+    ring = B.L2A_FLAG_RING_CACHE | B.L2A_FLAG_SKIP_GLOBAL
+    assert call(pp=B.make_params(2, 4096, 28, 4, 128, 4096, 1, B.L2A_BF16, ring)) == -3      # T < W + 1
+    assert call(pp=B.make_params(2, 4100, 28, 4, 128, 4096, 1, B.L2A_BF16, ring)) == -3      # not whole sub-blocks

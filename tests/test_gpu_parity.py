@@ -633,6 +633,42 @@ def test_decode_rows_behind_the_new_token_are_never_used(oracle, pos):
     decode_case(oracle, 2, 1024, 8, 2, 300, pos, 8, 0.6, seed=95, poison=True)
 
 
+@pytest.mark.parametrize("Tring,W,pos", [(320, 300, [5, 299]), (320, 300, [319, 320]), (320, 300, [1000, 4000]),
+                                          (512, 300, [511, 512]), (640, 100, [90, 5000]), (32, 31, [31, 32]),
+                                          (64, 31, [63, 100]), (4128, 4096, [4127, 9000])])
+def test_decode_local_ring_cache(oracle, Tring, W, pos):
+    """A Local module of its own keeps a ring of Tring >= W + 1 slots, token j in slot j mod Tring; the
+    result is the Local attention of the layer's definition at the token's position in the whole sequence."""
+    Bn, Hq, Hkv, D, Tfull = 2, 8, 2, 128, max(pos) + 1
+    k = gen.normal_tensor((Bn, Tfull, Hkv, D), 96, 1, "bf16")
+    v = gen.normal_tensor((Bn, Tfull, Hkv, D), 96, 2, "bf16")
+    qn = gen.normal_tensor((Bn, Hq, D), 96, 3, "bf16")
+    pos = np.asarray(pos, dtype=np.int32)
+    qfull = np.zeros((Bn, Tfull, Hq, D), np.float32)
+    for b in range(Bn):
+        qfull[b, pos[b]] = qn[b]
+    pr = oracle.Problem(qfull, k, v, np.zeros((Bn, 1, Tfull), np.uint8), W)
+    rows = np.array([(b, h, pos[b]) for b in range(Bn) for h in range(Hq)], dtype=np.int32)
+    ref = oracle.fwd_rows(pr, rows)
+    # the ring as the module would have written it: every token up to pos in its slot, later ones overwrite
+    kr = torch.full((Bn, Tring, Hkv, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    vr = torch.full((Bn, Tring, Hkv, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kd, vd = to_device(k, "bf16"), to_device(v, "bf16")
+    for b in range(Bn):
+        first = max(0, int(pos[b]) - Tring + 1)
+        j = torch.arange(first, int(pos[b]) + 1, device="cuda")
+        kr[b, j % Tring] = kd[b, j]
+        vr[b, j % Tring] = vd[b, j]
+    p = B.make_params(Bn, Tring, Hq, Hkv, D, W, 1, B.L2A_BF16, B.L2A_FLAG_SKIP_GLOBAL | B.L2A_FLAG_RING_CACHE)
+    O = torch.full((Bn, Hq, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    lse_l = torch.zeros((Bn, Hq), dtype=torch.float32, device="cuda")
+    B.l2a_attn_decode(p, to_device(qn, "bf16"), kr, vr, torch.from_numpy(pos).cuda(),
+                      torch.zeros((Bn, 1), dtype=torch.uint8, device="cuda"), O, lse_l, None)
+    torch.cuda.synchronize()
+    assert_close("O", to_host(O), ref["S"].reshape(Bn, Hq, D), "bf16")
+    assert_lse("lse_local", lse_l.cpu().numpy().astype(np.float64), ref["lse_l"].reshape(Bn, Hq), "bf16")
+
+
 @pytest.mark.timeout(600)
 def test_decode_full_length_cache(oracle):
     """Qwen2.5-7B head layout, 128K cache, a routed and an unrouted sequence; the cache rows behind
