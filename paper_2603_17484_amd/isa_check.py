@@ -7,7 +7,9 @@ sits between the matrix instruction and the first reader it has emitted too few 
 wave-uniform `if` per score element in the decode kernel: 3 wait states, wrong scores).  This
 script compiles the matrix-core kernels to assembly and walks every path of up to a dozen
 instructions behind each matrix instruction, through branches and their targets; a reader reached
-across a branch in fewer than 11 wait states is reported.
+across a branch in fewer than 11 wait states is reported.  Matrix instructions whose result tile
+lies in VGPRs are the kernels' own inline assembly, which the compiler does not pad at all: for
+them a reader in fewer than 11 wait states is reported on straight-line paths as well.
 
     python -m paper_2603_17484_amd.isa_check        # prints findings, exit status 1 if any
 """
@@ -43,7 +45,8 @@ def _instructions(text):
 
 
 def scan(text):
-    """[(matrix instruction, reader, wait states)] for readers reached too early across a branch."""
+    """[(matrix instruction, reader, wait states)] for readers reached too early: across a branch, or
+    anywhere behind a matrix instruction with a VGPR destination (inline assembly)."""
     ins = _instructions(text)
     label = {}
     for i, s in enumerate(ins):
@@ -81,7 +84,7 @@ def scan(text):
                     stores = op.startswith(("ds_write", "global_store", "scratch_store", "buffer_store"))
                     srcs = set().union(*[_regs(x) for k, x in enumerate(toks) if k > 0 or stores] or [set()])
                 if srcs & dst:
-                    if crossed:
+                    if crossed or any(r[0] == "v" for r in dst):
                         found.setdefault(origin, (ins[origin], t, ws))
                     return
                 if toks and _regs(toks[0]) & dst and op.startswith("v_") and not op.startswith("v_mfma"):

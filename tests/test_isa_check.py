@@ -44,6 +44,19 @@ def test_scanner_finds_a_result_read_too_early_across_a_branch():
     assert reader.startswith("v_accvgpr_read_b32 v83, a79") and wait_states == 3
 
 
+INLINE_ASM = """
+	v_mfma_f32_32x32x16_bf16 v[210:225], v[14:17], v[226:229], 0
+	v_fma_f32 v16, s3, v210, v0
+	s_endpgm
+"""
+
+
+def test_scanner_checks_vgpr_results_on_straight_paths_too():
+    """A result tile in VGPRs comes from the kernels' inline assembly, which the compiler never pads."""
+    hits = isa_check.scan(INLINE_ASM)
+    assert len(hits) == 1 and hits[0][2] == 0
+
+
 def test_scanner_accepts_padded_code_and_accumulation_chains():
     assert isa_check.scan(STRAIGHT) == []
 
