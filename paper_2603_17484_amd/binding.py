@@ -99,8 +99,8 @@ def torch_dtype(p: l2a_params):
     return torch.bfloat16 if p.dtype == L2A_BF16 else torch.float32
 
 
-def _ws(nbytes: int, device) -> Optional[torch.Tensor]:
-    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device) if nbytes else None
+def _ws(nbytes: int, device, alloc=None) -> Optional[torch.Tensor]:
+    return (alloc or torch.empty)(max(nbytes, 16), dtype=torch.uint8, device=device) if nbytes else None
 
 
 # ------------------------------------------------------------------------------------------
@@ -179,33 +179,39 @@ def profile_read(max_records: int = 4096):
 # ------------------------------------------------------------------------------------------
 # buffer helpers (allocation only)
 # ------------------------------------------------------------------------------------------
-def alloc_route(p: l2a_params, device="cuda"):
+# `alloc` has torch.empty's signature (shape, dtype=, device=); the tests pass one that surrounds every
+# buffer with guard bands.
+def alloc_route(p: l2a_params, device="cuda", alloc=None):
+    e = alloc or torch.empty
     G = p.Hq // p.Hkv
-    row_idx = torch.empty((p.B, p.Hkv, p.T * G), dtype=torch.int32, device=device)
-    count = torch.empty((p.B, p.Hkv), dtype=torch.int32, device=device)
-    first = torch.empty((p.B, p.Hkv, lib().l2a_kblk_entries(p.T)), dtype=torch.int32, device=device)
-    ws = _ws(lib().l2a_route_workspace_bytes(ctypes.byref(p)), device)
+    row_idx = e((p.B, p.Hkv, p.T * G), dtype=torch.int32, device=device)
+    count = e((p.B, p.Hkv), dtype=torch.int32, device=device)
+    first = e((p.B, p.Hkv, lib().l2a_kblk_entries(p.T)), dtype=torch.int32, device=device)
+    ws = _ws(lib().l2a_route_workspace_bytes(ctypes.byref(p)), device, alloc)
     return row_idx, count, first, ws
 
 
-def alloc_fwd(p: l2a_params, device="cuda", branches=True):
+def alloc_fwd(p: l2a_params, device="cuda", branches=True, alloc=None):
+    e = alloc or torch.empty
     dt = torch_dtype(p)
-    O = torch.empty((p.B, p.T, p.Hq, p.D), dtype=dt, device=device)
-    lse_l = torch.empty((p.B, p.Hq, p.T), dtype=torch.float32, device=device)
-    lse_g = torch.empty((p.B, p.Hq, p.T), dtype=torch.float32, device=device)
-    S = torch.empty_like(O) if branches else None
-    A = torch.empty_like(O) if branches else None
+    shape = (p.B, p.T, p.Hq, p.D)
+    O = e(shape, dtype=dt, device=device)
+    lse_l = e((p.B, p.Hq, p.T), dtype=torch.float32, device=device)
+    lse_g = e((p.B, p.Hq, p.T), dtype=torch.float32, device=device)
+    S = e(shape, dtype=dt, device=device) if branches else None
+    A = e(shape, dtype=dt, device=device) if branches else None
     return O, lse_l, lse_g, S, A
 
 
-def alloc_fwd_workspace(p: l2a_params, device="cuda"):
-    return _ws(lib().l2a_attn_workspace_bytes(ctypes.byref(p), 0), device)
+def alloc_fwd_workspace(p: l2a_params, device="cuda", alloc=None):
+    return _ws(lib().l2a_attn_workspace_bytes(ctypes.byref(p), 0), device, alloc)
 
 
-def alloc_bwd(p: l2a_params, device="cuda"):
+def alloc_bwd(p: l2a_params, device="cuda", alloc=None):
+    e = alloc or torch.empty
     dt = torch_dtype(p)
-    dq = torch.empty((p.B, p.T, p.Hq, p.D), dtype=dt, device=device)
-    dk = torch.empty((p.B, p.T, p.Hkv, p.D), dtype=dt, device=device)
-    dv = torch.empty_like(dk)
-    ws = _ws(lib().l2a_attn_workspace_bytes(ctypes.byref(p), 1), device)
+    dq = e((p.B, p.T, p.Hq, p.D), dtype=dt, device=device)
+    dk = e((p.B, p.T, p.Hkv, p.D), dtype=dt, device=device)
+    dv = e((p.B, p.T, p.Hkv, p.D), dtype=dt, device=device)
+    ws = _ws(lib().l2a_attn_workspace_bytes(ctypes.byref(p), 1), device, alloc)
     return dq, dk, dv, ws

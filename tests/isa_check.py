@@ -11,7 +11,15 @@ across a branch in fewer than 11 wait states is reported.  Matrix instructions w
 lies in VGPRs are the kernels' own inline assembly, which the compiler does not pad at all: for
 them a reader in fewer than 11 wait states is reported on straight-line paths as well.
 
-    python -m paper_2603_17484_amd.isa_check        # prints findings, exit status 1 if any
+A following matrix instruction counts as a reader through any of its operands: SrcA, SrcB, and
+SrcC or a destination that overlaps the tile, unless it is the accumulation form (destination and
+SrcC both exactly the tile), which the hardware interlocks.  A path that is still inside the hazard
+window when the branch-depth limit is reached is reported too, never dropped silently.
+
+Test and build infrastructure, not part of the product package: `__graft_entry__.build()` runs
+check_all() after compiling and fails on any finding; `tests/test_isa_check.py` does the same.
+
+    python -m tests.isa_check        # prints findings, exit status 1 if any
 """
 import os
 import re
@@ -19,11 +27,12 @@ import subprocess
 import sys
 import tempfile
 
-from .build import CSRC, FLAGS, HIPCC
+from paper_2603_17484_amd.build import CSRC, FLAGS, HIPCC
 
 KERNEL_SOURCES = ["attn_fwd_bf16.hip", "attn_bwd_dq_bf16.hip", "attn_bwd_dkdv_bf16.hip", "attn_decode_bf16.hip"]
 WAIT_STATES = 11      # 8-pass matrix instruction -> read of its result by another unit
 MAX_BRANCH_DEPTH = 6
+DEPTH_LIMIT = "<branch depth limit reached inside the hazard window>"
 
 
 def _regs(tok):
@@ -56,7 +65,10 @@ def scan(text):
     found = {}
 
     def walk(j, ws, dst, crossed, depth, origin):
-        while j < len(ins) and ws < WAIT_STATES and depth < MAX_BRANCH_DEPTH:
+        if depth >= MAX_BRANCH_DEPTH and ws < WAIT_STATES and j < len(ins):
+            found.setdefault(origin, (ins[origin], DEPTH_LIMIT, ws))
+            return
+        while j < len(ins) and ws < WAIT_STATES:
             t = ins[j]
             if t.startswith(".LBB"):
                 j += 1
@@ -77,9 +89,10 @@ def scan(text):
                 ws += 1
             else:
                 if op.startswith("v_mfma"):
-                    if _regs(toks[0]) & dst:
-                        return                      # accumulating into the same registers is interlocked
-                    srcs = set().union(*[_regs(x) for x in toks[1:3]])
+                    d2, c2 = _regs(toks[0]), (_regs(toks[3]) if len(toks) > 3 else set())
+                    if d2 == dst and c2 == dst:
+                        return                      # accumulating into the same tile is interlocked
+                    srcs = set().union(*[_regs(x) for x in toks[1:3]]) | c2 | d2
                 else:
                     stores = op.startswith(("ds_write", "global_store", "scratch_store", "buffer_store"))
                     srcs = set().union(*[_regs(x) for k, x in enumerate(toks) if k > 0 or stores] or [set()])

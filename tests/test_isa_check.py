@@ -1,7 +1,7 @@
 """The compiled matrix-core kernels are scanned for results of matrix instructions that are read
 too early on the far side of a branch (a case the compiler's own padding has missed; see
-paper_2603_17484_amd/isa_check.py).  CPU only: hipcc cross-compiles to assembly."""
-from paper_2603_17484_amd import isa_check
+tests/isa_check.py).  CPU only: hipcc cross-compiles to assembly."""
+from tests import isa_check
 
 PLANTED = """
 .LBB0_1:
@@ -55,6 +55,35 @@ def test_scanner_checks_vgpr_results_on_straight_paths_too():
     """A result tile in VGPRs comes from the kernels' inline assembly, which the compiler never pads."""
     hits = isa_check.scan(INLINE_ASM)
     assert len(hits) == 1 and hits[0][2] == 0
+
+
+SRC_C = """
+	v_mfma_f32_32x32x16_bf16 v[210:225], v[14:17], v[226:229], 0
+	v_mfma_f32_32x32x16_bf16 v[100:115], v[14:17], v[226:229], v[210:225]
+	s_endpgm
+"""
+
+RESTART = """
+	v_mfma_f32_32x32x16_bf16 v[210:225], v[14:17], v[226:229], 0
+	v_mfma_f32_32x32x16_bf16 v[210:225], v[18:21], v[230:233], 0
+	s_endpgm
+"""
+
+DEEP = "\n\tv_mfma_f32_32x32x16_bf16 v[210:225], v[14:17], v[226:229], 0\n" + "".join(
+    f"\ts_cbranch_scc1 .LBB0_{i}\n.LBB0_{i}:\n" for i in range(1, 9)) + "\tv_mov_b32_e32 v1, v210\n\ts_endpgm\n"
+
+
+def test_scanner_counts_srcc_and_overlapping_destinations_of_other_matrix_instructions():
+    """Another matrix instruction reads the tile as SrcC into a different destination, or restarts the
+    same destination from zero: neither is the interlocked accumulation form."""
+    assert len(isa_check.scan(SRC_C)) == 1
+    assert len(isa_check.scan(RESTART)) == 1
+
+
+def test_scanner_reports_the_branch_depth_limit():
+    """Eight nested branches inside the hazard window: the walk gives up at depth 6 and must say so."""
+    hits = isa_check.scan(DEEP)
+    assert len(hits) == 1 and hits[0][1] == isa_check.DEPTH_LIMIT and hits[0][2] < isa_check.WAIT_STATES
 
 
 def test_scanner_accepts_padded_code_and_accumulation_chains():
