@@ -77,6 +77,9 @@ int router_decide(const l2a_params& p, int C, const void* x, const float* w, flo
 // ---- util.hip
 int row_deltas(const Geom& g, int dtype, const void* dO, const void* S, const void* A, float* delta_l,
                float* delta_g, hipStream_t st);
+// bf16: delta of the first 64 tokens of every sequence recomputed from its definition (one branch)
+int head_deltas(const Geom& g, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+                float* delta, int local, hipStream_t st);
 int fill_zero(void* ptr, size_t bytes, hipStream_t st);
 int fill_f32(float* ptr, size_t n, float value, hipStream_t st);
 

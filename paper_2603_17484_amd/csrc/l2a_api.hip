@@ -286,6 +286,10 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
     if ((r = row_deltas(g, p->dtype, dO, do_local ? S : nullptr, do_global ? A : nullptr, delta_l, delta_g, st)) !=
         L2A_OK)
         return r;
+    if (p->dtype == L2A_BF16) {  // outputs saved in bf16: the first tokens' deltas come from the definition instead
+        if (do_local && (r = head_deltas(g, q_loc, k_loc, v_loc, dO, lse_local, delta_l, 1, st)) != L2A_OK) return r;
+        if (do_global && (r = head_deltas(g, q_glb, k_glb, v_glb, dO, lse_global, delta_g, 0, st)) != L2A_OK) return r;
+    }
 
     const RowSet rs_l{nullptr, nullptr, nullptr, 1};
     const RowSet rs_g = dense ? RowSet{nullptr, nullptr, nullptr, 0} : RowSet{row_idx, count, kblk_first_row, 0};

@@ -1,6 +1,8 @@
 // Small memory-bound helpers: the backward pass's per-row dot products and fills.
 #include "common.hpp"
 
+#include <algorithm>
+
 namespace l2a {
 namespace {
 
@@ -60,6 +62,42 @@ __global__ __launch_bounds__(kThreads) void row_deltas_kernel(Geom gm, const E* 
     }
 }
 
+// delta of the first tokens of a sequence, from its definition instead of from the saved outputs:
+//     delta_t = sum_j p_tj <dO_t, v_j>,   p_tj = exp(scale <q_t, k_j> - lse_t)     (= <dO_t, out_t>).
+// The saved outputs are bf16: <dO_t, out_t> then carries an error of about 2^-9 sqrt(D) |dO_t| |out_t|,
+// which enters dq_t as  scale * error * sum_j p_tj k_j.  Both factors shrink like 1 / sqrt(keys) for
+// rows that average many keys, but for the first few tokens they do not (token 2 with N(0,1) inputs:
+// up to 1.2e-2 per branch, twice that when both branches read the same tensors, since s_t = a_t
+// there), so the first kHeadTokens deltas are recomputed exactly.  One wavefront per (token, head);
+// lane = key.  A row whose log-sum-exp is -inf (not routed: a_t = 0) gets delta = 0.
+constexpr int kHeadTokens = 64;
+
+__global__ __launch_bounds__(64) void head_deltas_kernel(Geom gm, const __bf16* __restrict__ q,
+                                                         const __bf16* __restrict__ k, const __bf16* __restrict__ v,
+                                                         const __bf16* __restrict__ dO, const float* __restrict__ lse,
+                                                         float* __restrict__ delta, int local) {
+    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z, j = threadIdx.x;
+    const int hk = h / gm.G;
+    const size_t so = ((size_t)b * gm.Hq + h) * gm.T + t;
+    const float l = lse[so];
+    float term = 0.f;
+    const bool in_reach = j <= t && (!local || t - j <= gm.W);
+    if (in_reach && l != -INFINITY) {
+        const __bf16* qr = q + (((size_t)b * gm.T + t) * gm.Hq + h) * gm.D;
+        const __bf16* gr = dO + (((size_t)b * gm.T + t) * gm.Hq + h) * gm.D;
+        const __bf16* kr = k + (((size_t)b * gm.T + j) * gm.Hkv + hk) * gm.D;
+        const __bf16* vr = v + (((size_t)b * gm.T + j) * gm.Hkv + hk) * gm.D;
+        float s = 0.f, dp = 0.f;
+        for (int c = 0; c < gm.D; ++c) {
+            s = fmaf((float)qr[c], (float)kr[c], s);
+            dp = fmaf((float)gr[c], (float)vr[c], dp);
+        }
+        term = expf(s * gm.scale - l) * dp;
+    }
+    for (int o = 32; o > 0; o >>= 1) term += __shfl_xor(term, o);
+    if (j == 0) delta[so] = term;
+}
+
 __global__ __launch_bounds__(kThreads) void fill_u32_kernel(uint32_t* p, size_t n, uint32_t value) {
     size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * kThreads;
@@ -88,6 +126,16 @@ int row_deltas(const Geom& g, int dtype, const void* dO, const void* S, const vo
         hipLaunchKernelGGL((row_deltas_kernel<__bf16, 8>), grid, dim3(kThreads), lds, st, g, (const __bf16*)dO, (const __bf16*)S, (const __bf16*)A, delta_l, delta_g, tok);
     else
         return L2A_ERR_UNSUPPORTED;
+    return launch_status();
+}
+
+int head_deltas(const Geom& g, const void* q, const void* k, const void* v, const void* dO, const float* lse,
+                float* delta, int local, hipStream_t st) {
+    static_assert(kHeadTokens <= 64, "one lane per key");
+    const dim3 grid((unsigned)std::min(g.T, kHeadTokens), (unsigned)g.Hq, (unsigned)g.B);
+    KernelTimer kt("head_deltas", st);
+    hipLaunchKernelGGL(head_deltas_kernel, grid, dim3(64), 0, st, g, (const __bf16*)q, (const __bf16*)k,
+                       (const __bf16*)v, (const __bf16*)dO, lse, delta, local);
     return launch_status();
 }
 
