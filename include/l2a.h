@@ -60,7 +60,8 @@ enum {
     L2A_ERR_UNSUPPORTED = -3, /* dtype / D combination or flag combination not built */
     L2A_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than l2a_*_workspace_bytes() */
     L2A_ERR_ALIGN = -5,       /* a data pointer is not 16-byte aligned */
-    L2A_ERR_LAUNCH = -6       /* the HIP runtime refused a launch (hipGetLastError) */
+    L2A_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch (hipGetLastError) */
+    L2A_ERR_STATIC_LIMIT = -7 /* the problem needs more scratch than a *_static entry point's fixed array holds */
 };
 
 typedef struct l2a_params {
@@ -113,6 +114,25 @@ int32_t l2a_kblk_entries(int32_t T);
  */
 int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
                       int32_t* kblk_first_row, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * l2a_route_compact for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same
+ * outputs, same bits as l2a_route_compact; the per-chunk counts live in a fixed array in the library's
+ * device image instead of a caller workspace, and the call allocates nothing (no hipMalloc, no hipFree).
+ *   Limit   B * Hkv * ceil(T / c) <= 65536 counters, c = 2048 positions (256 for T <= 16384) -- e.g.
+ *           B * Hkv = 32 at T = 4M tokens; beyond it the call returns L2A_ERR_STATIC_LIMIT and
+ *           launches nothing.  The array (256 KB) stays resident on every GPU the library runs on
+ *           until the process ends.
+ *   Sharing every call on a GPU uses that GPU's one array and overwrites what the last call left (no
+ *           part of it has to start at zero: each counter is written before it is read).  Calls
+ *           that overlap on one GPU -- different streams, or different threads -- race; order
+ *           them on one stream or with events.
+ *   Set-up  the first call on a device looks up the array's address on that device
+ *           (hipGetSymbolAddress), so make it outside stream capture.  L2A_ERR_LAUNCH if that fails.
+ */
+int l2a_route_compact_static(const l2a_params* p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
+                             int32_t* kblk_first_row, void* stream);
 
 /*
  * Router front-end (Sec. 3.1 Eq. 3; the threshold is 0.5 in training and a knob at test time):

@@ -23,7 +23,7 @@ L2A_FLAG_RING_CACHE = 16
 L2A_FLAG_SCALAR = 1 << 16
 
 EXPORTS = ("l2a_version", "l2a_strerror", "l2a_route_workspace_bytes", "l2a_attn_workspace_bytes",
-           "l2a_kblk_entries", "l2a_route_compact", "l2a_router_decide", "l2a_attn_fwd", "l2a_attn_bwd",
+           "l2a_kblk_entries", "l2a_route_compact", "l2a_route_compact_static", "l2a_router_decide", "l2a_attn_fwd", "l2a_attn_bwd",
            "l2a_decode_workspace_bytes", "l2a_attn_decode",
            "l2a_profile_enable", "l2a_profile_read")
 
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.l2a_kblk_entries.argtypes = [ctypes.c_int32]
         L.l2a_route_compact.restype = ctypes.c_int
         L.l2a_route_compact.argtypes = [pp, vp, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+        L.l2a_route_compact_static.restype = ctypes.c_int
+        L.l2a_route_compact_static.argtypes = [pp, vp, i32p, i32p, i32p, vp]
         L.l2a_router_decide.restype = ctypes.c_int
         L.l2a_router_decide.argtypes = [pp, ctypes.c_int32, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
         L.l2a_decode_workspace_bytes.restype = ctypes.c_size_t
@@ -114,6 +116,15 @@ def l2a_route_compact(p: l2a_params, mask: torch.Tensor, row_idx: torch.Tensor, 
                                  _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream())
     if rc != 0:
         raise L2AError(rc, "l2a_route_compact")
+
+
+def l2a_route_compact_static(p: l2a_params, mask: torch.Tensor, row_idx: torch.Tensor, count: torch.Tensor,
+                             kblk_first_row: torch.Tensor) -> None:
+    """l2a_route_compact with the library's static scratch: no workspace, nothing allocated."""
+    rc = lib().l2a_route_compact_static(ctypes.byref(p), _ptr(mask), _ptr(row_idx), _ptr(count),
+                                        _ptr(kblk_first_row), _stream())
+    if rc != 0:
+        raise L2AError(rc, "l2a_route_compact_static")
 
 
 def l2a_router_decide(p: l2a_params, x: torch.Tensor, w: torch.Tensor, bias: float, tau: float, mask: torch.Tensor,

@@ -43,6 +43,9 @@ struct KernelTimer {
 size_t route_workspace_bytes(const l2a_params& p);
 int route_compact(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
                   int32_t* kblk_first_row, void* ws, hipStream_t st);
+// the same with the chunk counts in the library's static device array
+int route_compact_static(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
+                         int32_t* kblk_first_row, hipStream_t st);
 
 // A forward branch kernel computes x = attention(row) for every row of `rs` and then
 //   main_out[row] = merge ? main_out[row] + x : x      (O)

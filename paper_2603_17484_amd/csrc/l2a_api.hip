@@ -98,6 +98,9 @@ const char* l2a_strerror(int code) {
         case L2A_ERR_WORKSPACE: return "workspace missing or too small";
         case L2A_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
         case L2A_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+        case L2A_ERR_STATIC_LIMIT:
+            return "problem too large for the library's static scratch (l2a_route_compact_static: more than 65536 "
+                   "chunk counters); use the entry point that takes a workspace";
         default: return "unknown error code";
     }
 }
@@ -125,6 +128,16 @@ int l2a_route_compact(const l2a_params* p, const uint8_t* mask, int32_t* row_idx
     if (!workspace || workspace_bytes < route_workspace_bytes(*p)) return L2A_ERR_WORKSPACE;
     if (misaligned(row_idx) || misaligned(workspace)) return L2A_ERR_ALIGN;
     return route_compact(*p, mask, row_idx, count, kblk_first_row, workspace, (hipStream_t)stream);
+}
+
+int l2a_route_compact_static(const l2a_params* p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
+                             int32_t* kblk_first_row, void* stream) {
+    const int rc = check_params(p);
+    if (rc != L2A_OK) return rc;
+    if (p->flags & L2A_FLAG_DENSE) return L2A_OK;
+    if (!mask || !row_idx || !count || !kblk_first_row) return L2A_ERR_NULL;
+    if (misaligned(row_idx)) return L2A_ERR_ALIGN;
+    return route_compact_static(*p, mask, row_idx, count, kblk_first_row, (hipStream_t)stream);
 }
 
 int l2a_router_decide(const l2a_params* p, int32_t C, const void* x, const float* w, float bias, float tau,

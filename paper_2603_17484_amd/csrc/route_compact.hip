@@ -10,6 +10,15 @@
 //      4-entry table in LDS.  Rows are written in ascending order, the unused tail gets -1.
 #include "common.hpp"
 
+#include <mutex>
+
+// Scratch of l2a_route_compact_static: the per-chunk counts that l2a_route_compact keeps in the
+// caller's workspace.  Every GPU the library runs on holds its own copy of this array, at its own
+// address, until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress -- never a device address -- so the host side uses static_scratch_ptr().
+constexpr int kStaticCounters = 65536;  // 256 KB: (b, KV head, chunk) triples of one call
+static __device__ __align__(256) int32_t scratch[kStaticCounters];
+
 namespace l2a {
 namespace {
 
@@ -140,6 +149,34 @@ size_t route_workspace_bytes(const l2a_params& p) {
     const size_t chunk = chunk_positions(p.T);
     const size_t nchunks = ((size_t)p.T + chunk - 1) / chunk;
     return sizeof(int32_t) * nchunks * (size_t)p.B * (size_t)p.Hkv;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int32_t* static_scratch_ptr() {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static int32_t* ptr[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr[dev] = (int32_t*)p;
+    }
+    return ptr[dev];
+}
+
+int route_compact_static(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, int32_t* count,
+                         int32_t* kblk_first_row, hipStream_t st) {
+    if (route_workspace_bytes(p) > sizeof(int32_t) * (size_t)kStaticCounters) return L2A_ERR_STATIC_LIMIT;
+    int32_t* ws = static_scratch_ptr();
+    if (!ws) return L2A_ERR_LAUNCH;
+    // every counter the second kernel reads is written by the first: nothing has to start at zero
+    return route_compact(p, mask, row_idx, count, kblk_first_row, ws, st);
 }
 
 int route_compact(const l2a_params& p, const uint8_t* mask, int32_t* row_idx, int32_t* count,

@@ -122,6 +122,27 @@ def test_null_alignment_and_workspace_errors(lib):
     assert lib.l2a_route_compact(ctypes.byref(p), None, None, None, None, None, 0, None) == 0
 
 
+def test_static_scratch_entry_point_argument_errors(lib):
+    """l2a_route_compact_static: the checks of l2a_route_compact minus the workspace, plus the fixed
+    array's limit of 65536 chunk counters -- all answered before anything touches a GPU."""
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    p = B.make_params(1, 256, 4, 2, 128, 16)
+    pp = ctypes.byref(p)
+    assert lib.l2a_route_compact_static(None, ok, ok, ok, ok, None) == -1
+    assert lib.l2a_route_compact_static(pp, None, ok, ok, ok, None) == -1
+    assert lib.l2a_route_compact_static(pp, ok, odd, ok, ok, None) == -5
+    bad = B.make_params(1, 0, 4, 2, 128, 16)
+    assert lib.l2a_route_compact_static(ctypes.byref(bad), ok, ok, ok, ok, None) == -2
+    # 64 x 32 (batch, KV head) pairs x 64 chunks of 256 positions = 131072 counters
+    big = B.make_params(64, 16384, 32, 32, 128, 16)
+    assert lib.l2a_route_workspace_bytes(ctypes.byref(big)) == 4 * 131072
+    assert lib.l2a_route_compact_static(ctypes.byref(big), ok, ok, ok, ok, None) == -7
+    assert b"static scratch" in lib.l2a_strerror(-7)
+    # exactly at the limit the size check passes (what follows needs a GPU, so only the dense no-op is called here)
+    p.flags = B.L2A_FLAG_DENSE
+    assert lib.l2a_route_compact_static(ctypes.byref(p), None, None, None, None, None) == 0
+
+
 def test_router_argument_errors(lib):
     p = B.make_params(1, 128, 4, 2, 128, 16)
     x = ctypes.c_void_p(0x1000)
