@@ -22,12 +22,13 @@
 // (slots 0-15) and the dV, dK update of this tile (slots 16-31) run on the matrix cores while the
 // VALU turns this tile's S, dP into P and dS.
 #include "tiles.hpp"
+#include "dkdv_walk.hpp"
 
 namespace l2a {
 namespace {
 
-constexpr int kKeysPerWg = 128;
-constexpr int kRT = 32;     // rows per tile
+using walk::kKeysPerWg;
+using walk::kRT;  // rows per tile
 constexpr int kAhead = 3;   // operand look-ahead, in slots
 constexpr int kNB = 8;              // LDS buffers: loads run kNB - 1 tiles ahead
 constexpr int kDmaPerStep = 7;      // direct-to-LDS instructions a wavefront issues per tile step
@@ -81,17 +82,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
 
     const Geom& gm = a.gm;
     const int bh = blockIdx.y, b = bh / gm.Hkv, hk = bh - b * gm.Hkv;
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Key blocks are handed
-    // out in chunks of adjacent blocks per XCD, so that the workgroups resident on one XCD stream
-    // nearly the same rows at the same time; successive rounds of chunks visit the XCDs in snake
-    // order, which evens out the causal triangle's work between them.
-    int kblk;
-    {
-        const int x = (int)blockIdx.x & 7, j = (int)blockIdx.x >> 3;
-        const int round = j / a.chunk, w = j % a.chunk;
-        const int xx = (round & 1) ? 7 - x : x;
-        kblk = (round * 8 + xx) * a.chunk + w;
-    }
+    const int kblk = walk::key_block((int)blockIdx.x, a.chunk);  // XCD-aware: chunks of neighbours, snake order
     const int k0 = kblk * kKeysPerWg;
     if (k0 >= a.gm.T) return;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -111,105 +102,29 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
         }
     }
 
-    // ---- per set: the 32-row tiles that can see this block of keys, split in three runs: a head
-    // whose rows may lie before some key (causal mask), a middle that needs no mask, a tail
-    // (sliding-window edge, ragged end).  Tile t of a set covers rows 32 t .. 32 t + 31.
-    auto tile_runs = [&](int s, int& tb, int& th, int& tt, int& te) __attribute__((always_inline)) {
-        tb = th = tt = te = 0;
-        if (s >= a.nsets) return;
+    // ---- per set: the 32-row tiles that can see this block of keys, in three runs (causal-masked head,
+    // unmasked middle, window / ragged tail), and the order they are walked in (dkdv_walk.hpp)
+    auto tile_runs = [&](int s) __attribute__((always_inline)) {
+        if (s >= a.nsets) return walk::Runs{0, 0, 0, 0};
         const RowSet& rs = a.rs[s];
-        int rb, re, r_mid;
-        const int kend = k0 + kKeysPerWg;  // rows at positions >= kend see every key of the block
-        if (rs.local) {
-            rb = k0 * gm.G;
-            re = min(gm.T, kend + gm.W) * gm.G;
-            r_mid = kend * gm.G;
-        } else if (!rs.kblk_first_row) {  // dense: identity rows
-            rb = k0 * gm.G;
-            re = gm.T * gm.G;
-            r_mid = kend * gm.G;
-        } else {
+        int kind = rs.local ? walk::kLocalRows : walk::kDenseRows, f_lo = 0, f_hi = 0, rows = gm.T * gm.G;
+        if (!rs.local && rs.kblk_first_row) {
             const int32_t* first = rs.kblk_first_row + (size_t)bh * (nkb + 1);
-            re = rows_total(rs, gm, bh);  // clamped like the entries of `first`: device data
-            rb = min(max(first[k0 >> 6], 0), re);
-            r_mid = min(max(first[min(kend >> 6, nkb)], rb), re);
+            kind = walk::kListRows;
+            rows = rows_total(rs, gm, bh);  // clamped like the entries of `first`: device data
+            f_lo = first[k0 >> 6];
+            f_hi = first[min((k0 + kKeysPerWg) >> 6, nkb)];
         }
-        if (kend > gm.T) r_mid = re;  // keys past the end of the sequence: mask everywhere
-        if (re <= rb) return;
-        tb = rb / kRT;
-        te = (re + kRT - 1) / kRT;
-        th = min(te, max(tb, (r_mid + kRT - 1) / kRT));
-        int tl = (re % kRT) ? te - 1 : te;
-        if (rs.local) {
-            const long long r_suf = (long long)(k0 + gm.W + 1) * gm.G;  // first row whose window starts after k0
-            if (r_suf < re) tl = min(tl, (int)(r_suf / kRT));
-        }
-        tt = max(tl, th);
-        if (a.nsplit > 1) {  // this workgroup's share of the tiles
-            const int nt = te - tb, z = blockIdx.z;
-            const int b2 = tb + (int)((long long)nt * z / a.nsplit), e2 = tb + (int)((long long)nt * (z + 1) / a.nsplit);
-            tb = b2, te = e2;
-            th = min(max(th, tb), te);
-            tt = min(max(tt, th), te);
-        }
+        return walk::tile_runs(kind, k0, gm.T, gm.G, gm.W, f_lo, f_hi, rows, a.nsplit, (int)blockIdx.z);
     };
-    int tb0, th0, tt0, te0, tb1, th1, tt1, te1;
-    tile_runs(0, tb0, th0, tt0, te0);
-    tile_runs(1, tb1, th1, tt1, te1);
-    const int n0 = te0 - tb0, n1 = te1 - tb1;
-    const int total = n0 + n1;
+    const walk::Plan plan = walk::make_plan(a.nsets, tile_runs(0), a.rs[0].local != 0, tile_runs(1),
+                                            a.nsets > 1 && a.rs[1].local != 0, kblk, a.chunk, gm.T, gm.G, a.set_stride);
+    const int total = plan.total;
 
-    // ---- loads.  Flat tile index it -> (set, tile)
+    // ---- loads.  A cursor names the tile of each step (advanced once per step, branch-free)
     const unsigned lds_rm0 = lds_offset(&lds_rm[0]);
-    // A Global set is walked downwards from its last tile, so that all key blocks of a head read the
-    // same tile at the same step (they only stop at different tiles).  A Local set is walked upwards,
-    // but every key block of an XCD's chunk starts at the first tile of the chunk's *last* key block
-    // and wraps around to its own first tiles at the end: the ranges of neighbouring key blocks are
-    // shifted copies of each other, and this rotation makes them meet on the same tile at the same step.
-    const bool rev0 = a.rs[0].local == 0, rev1 = a.nsets > 1 && a.rs[1].local == 0;
-    auto rotation = [&](int s, int tb, int n) __attribute__((always_inline)) {
-        if (s >= a.nsets || !a.rs[s].local || n <= 0) return 0;
-        const int nblk = (gm.T + kKeysPerWg - 1) / kKeysPerWg;
-        const int last = min((kblk / a.chunk) * a.chunk + a.chunk - 1, nblk - 1);
-        const int r = (int)(((long long)last * kKeysPerWg * gm.G) / kRT) - tb;
-        return (r >= 0 && r < n) ? r : 0;  // ranges that do not overlap share nothing
-    };
-    const int rot0 = rotation(0, tb0, n0), rot1 = rotation(1, tb1, n1);
-    // Loads walk the tiles with a cursor that is advanced once per step: tile te - 1 - j for a reversed
-    // set, tb + (j + rot) mod n otherwise; after the last tile of set 0 it moves on to set 1.  Past the
-    // very last tile it stays there: the steps near the end re-load that tile into buffers nobody reads
-    // any more, so that every step issues the same number of loads.
-    struct Cursor {
-        int t, left, tb, te, i;  // tile; tiles left in the set; the set's range (for the wrap); flat index
-        bool rev;
-        long long set;           // byte offset of the set's arrays
-    };
-    auto cursor_begin = [&]() __attribute__((always_inline)) {
-        Cursor c;
-        c.i = 0;
-        if (n0 > 0) {
-            c.left = n0, c.tb = tb0, c.te = te0, c.rev = rev0, c.set = 0;
-            c.t = rev0 ? te0 - 1 : tb0 + rot0;
-        } else {
-            c.left = n1, c.tb = tb1, c.te = te1, c.rev = rev1, c.set = a.set_stride;
-            c.t = rev1 ? te1 - 1 : tb1 + rot1;
-        }
-        return c;
-    };
-    const int t_set1 = rev1 ? te1 - 1 : tb1 + rot1;
-    auto advance = [&](Cursor& c) __attribute__((always_inline)) {  // branch-free: it runs between matrix instructions
-        const bool more = c.i + 1 < total;
-        const bool sw = more && c.left == 1;  // only set 0 can end before the last tile
-        int t1 = c.rev ? c.t - 1 : c.t + 1;
-        t1 = (!c.rev && t1 == c.te) ? c.tb : t1;
-        c.t = sw ? t_set1 : (more ? t1 : c.t);
-        c.left = sw ? n1 : (more ? c.left - 1 : c.left);
-        c.tb = sw ? tb1 : c.tb;
-        c.te = sw ? te1 : c.te;
-        c.rev = sw ? rev1 : c.rev;
-        c.set = sw ? a.set_stride : c.set;
-        c.i = more ? c.i + 1 : c.i;
-    };
+    using Cursor = walk::Cursor;
+    auto advance = [&](Cursor& c) __attribute__((always_inline)) { walk::cursor_advance(c, plan); };
     // Every load is a wave-uniform base plus a per-lane offset fixed for the whole kernel.
     const RmDma<kRT> rm_off = rm_tr_dma_setup<kRT>(kD * 2, wave);
     const unsigned stat_off = n * 4;
@@ -354,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
     if (total > 0) {
         // ---- prologue: tiles 0 .. kNB-2; S, dP of tile 0
         SdP Xa, Xb;
-        Cursor lc = cursor_begin();
+        Cursor lc = walk::cursor_begin(plan);
         static_for<0, kNB - 1>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             StepLoads L;
@@ -409,32 +324,16 @@ __global__ __launch_bounds__(kThreads) void bwd_dkdv_kernel(DkdvArgs a) {
                 flip = true;
             }
         };
-        // Segments in walking order; inside one the mask flag is constant.  Tiles [tb, th) need the
-        // causal mask, [th, tt) none, [tt, te) the window / ragged-end mask.
+        // Segments in walking order; inside one the mask flag is constant.
         int it0 = 0;
-        auto walk = [&](int s, int b, int e, bool local) __attribute__((always_inline)) {  // tiles [b, e) of set s
-            const int sth = s ? th1 : th0, stt = s ? tt1 : tt0;
-            const bool rev = s ? rev1 : rev0;
-#pragma unroll
-            for (int part = 0; part < 3; ++part) {
-                const int run_id = rev ? 2 - part : part;
-                const int lo = run_id == 0 ? b : max(b, run_id == 1 ? sth : stt);
-                const int hi = run_id == 0 ? min(e, sth) : (run_id == 1 ? min(e, stt) : e);
-                if (lo >= hi) continue;
-                if (run_id == 1)
-                    run(std::false_type{}, it0, it0 + (hi - lo), local);
-                else
-                    run(std::true_type{}, it0, it0 + (hi - lo), local);
-                it0 += hi - lo;
-            }
-        };
-        for (int s = 0; s < a.nsets; ++s) {
-            const int sb = s ? tb1 : tb0, se = s ? te1 : te0, rot = s ? rot1 : rot0;
+        walk::for_each_segment(plan, [&](int s, bool masked, int count) __attribute__((always_inline)) {
             const bool local = (s ? a.rs[1].local : a.rs[0].local) != 0;
-            if (sb >= se) continue;
-            walk(s, sb + rot, se, local);     // a reversed set has no rotation: the whole range
-            if (rot) walk(s, sb, sb + rot, local);
-        }
+            if (masked)
+                run(std::true_type{}, it0, it0 + count, local);
+            else
+                run(std::false_type{}, it0, it0 + count, local);
+            it0 += count;
+        });
         dma_wait();  // the last steps' loads (re-loads of the last tile) must land before the LDS is given up
     }
 
@@ -473,15 +372,8 @@ __global__ __launch_bounds__(kThreads) void dkdv_reduce_kernel(const float* __re
 
 }  // namespace
 
-// Workgroups per key block: short sequences have too few key blocks to fill the chip (one workgroup
-// per compute unit); their row tiles are then shared out until there are two per compute unit.
-int dkdv_splits(const Geom& g) {
-    const long long nblk = (g.T + kKeysPerWg - 1) / kKeysPerWg;
-    int z = 1;
-    if (nblk * g.B * g.Hkv >= 256) return z;  // a workgroup per compute unit: splitting gains nothing (measured)
-    while (z < 8 && nblk * g.B * g.Hkv * z < 512) z *= 2;
-    return z;
-}
+// Workgroups per key block (short sequences share a key block's row tiles between several)
+int dkdv_splits(const Geom& g) { return walk::launch_shape(g.T, (long long)g.B * g.Hkv).nsplit; }
 
 // packed[s]: compact copies of set s made by pack_rows (5 pointers in the order of PackedRows).
 // With two sets every array of the second must lie the same number of bytes after the first's.
@@ -505,13 +397,12 @@ int mfma_bwd_dkdv(const Geom& g, const RowSet* sets, int nsets, const void* cons
     a.v = (const __bf16*)v;
     a.dk = (__bf16*)dk;
     a.dv = (__bf16*)dv;
-    const int nblk = (g.T + kKeysPerWg - 1) / kKeysPerWg;
-    a.chunk = std::max(1, std::min(32, nblk / 32));
-    const int per = 8 * a.chunk;
-    a.nsplit = dkdv_splits(g);
+    const walk::LaunchShape shape = walk::launch_shape(g.T, (long long)g.B * g.Hkv);
+    a.chunk = shape.chunk;
+    a.nsplit = shape.nsplit;
     a.part = part;
     if (a.nsplit > 1 && !part) return L2A_ERR_WORKSPACE;
-    const dim3 grid((nblk + per - 1) / per * per, g.B * g.Hkv, a.nsplit);
+    const dim3 grid(shape.grid_x, g.B * g.Hkv, a.nsplit);
     {
         KernelTimer kt("bwd_dkdv", st);
         hipLaunchKernelGGL(bwd_dkdv_kernel, grid, dim3(kThreads), 0, st, a);
