@@ -27,6 +27,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 # dispatch) scaled by what the same counters read for a plain 1 GiB device copy (--calibrate-copy):
 # FETCH x 2.0, WRITE x 1.0.  The counters cannot be read from inside the process, so the figures of the
 # committed profile are repeated here; they are reported only for exactly that workload.
+TRAFFIC_SOURCE = ("NOT measured in this run: constant copied from profiles/all_kernels_train_128k_hbm_bytes.md, two "
+                  "rocprofv3 --pmc runs of `bench.py --sparse-only --calibrate-copy` on the same workload")
 MEASURED_TRAFFIC_BYTES = {"bwd_dkdv": 1.700e10, "bwd_dq_global": 1.746e10, "bwd_dq_local": 4.25e9,
                           "fwd_global": 1.487e10, "fwd_local": 5.40e9}
 
@@ -213,7 +215,7 @@ def main() -> int:
     ms_dense = None
     if not args.no_dense:
         dense = build(B.L2A_FLAG_DENSE)
-        ms_dense, _ = timed(dense, max(1, min(args.steps, 2)) if T > 32768 else args.steps, 1)
+        ms_dense, _ = timed(dense, max(1, min(args.steps, 5)) if T > 32768 else args.steps, 1)
         ms_dense_graph = None
         if args.graph:
             ms_dense_graph, _ = timed(dense, args.steps, 0, graph=True)
@@ -235,6 +237,7 @@ def main() -> int:
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if default_workload else None,
                 "traffic_unit": "HBM-side bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
+                "traffic_source": (TRAFFIC_SOURCE if default_workload else None),
                 "algorithmic_flops_per_launch": alg[dom], "avg_ms": round(kern[dom], 3)}
 
     # ---- CPU oracle on a bounded sample of the same workload
@@ -357,8 +360,10 @@ def decode_leg(torch, B, w, dev, g, batch=8):
 
 def cpu_baseline(w, q, k, v, dO, mask_np, backward, seed, budget_s=15.0):
     """The CPU oracle, as it stands, on sampled routed rows of the same tensors: forward of both
-    branches plus the dQ pass.  Rate in algorithmic FLOPs (4 D forward + 6 D for the dQ pass per
-    (row, key) pair the oracle visited), so the unit matches `value`."""
+    branches plus the dQ pass.  No dK/dV pass is run (a key's gradient needs the statistics of every
+    row that can see it, i.e. a forward over most of the sequence).  Rate in algorithmic FLOPs of what the
+    sample produces -- 4 D per (row, key) pair for the forward, 4 D for dP and dQ -- so the unit matches
+    `value`; the scores the dQ pass recomputes are not counted."""
     import torch
     from oracle import l2a_oracle as orc
     orc.build()
@@ -385,11 +390,13 @@ def cpu_baseline(w, q, k, v, dO, mask_np, backward, seed, budget_s=15.0):
     dt, pairs = run(pick(256))
     n = int(max(256, min(40000, 256 * budget_s / max(dt, 1e-3))))
     dt, pairs = run(pick(n))
-    per_pair = (10.0 if backward else 4.0) * w.D
+    per_pair = (8.0 if backward else 4.0) * w.D
     threads = orc.threads()
     return {"value": round(per_pair * pairs / dt / 1e12, 6), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "sample": f"{n} routed rows drawn uniformly: oracle forward (local+global) "
-                      f"{'and dQ pass ' if backward else ''}over {pairs:.3e} (row,key) pairs in {dt:.1f} s"}
+                      f"{'and dQ pass ' if backward else ''}over {pairs:.3e} (row,key) pairs in {dt:.1f} s; "
+                      f"{'no dK/dV pass is run; ' if backward else ''}valued at {per_pair / w.D:.0f} D FLOP per pair "
+                      f"(forward 4 D{', dP and dQ 4 D' if backward else ''})"}
 
 
 if __name__ == "__main__":

@@ -22,7 +22,12 @@
  *     stream) and no call synchronises with the host.
  *   - Tensors are contiguous, row-major:  q, O, dO, dq, S, A : [B, T, Hq, D];
  *     k, v, dk, dv : [B, T, Hkv, D];  lse_* : [B, Hq, T] float.  Element type is bf16
- *     (L2A_BF16, fp32 accumulation, D = 128) or float (L2A_FP32, D = 64 or 128).
+ *     (L2A_BF16, fp32 accumulation, D = 128; D = 64 only together with L2A_FLAG_SCALAR, otherwise
+ *     L2A_ERR_UNSUPPORTED) or float (L2A_FP32, D = 64 or 128).  There are no stride arguments: the
+ *     kernels fill their LDS tiles with direct global->LDS loads whose per-lane offsets are fixed
+ *     for the whole kernel from these row sizes, and the pre-passes that would absorb another
+ *     layout are exactly the copies a caller with strided views would otherwise make itself.
+ *   - Hq / Hkv <= 16.
  *   - Grouped-query attention: query head h reads KV head h / G, G = Hq / Hkv.
  *   - Log-sum-exp values are natural logs of sum_j exp(scale <q,k_j>).
  *   - Return value: 0 on success, a negative L2A_ERR_* otherwise.  On an argument error
@@ -50,7 +55,7 @@ enum {
                                  l2a_attn_fwd: short sequences otherwise run them in one launch) */
     L2A_FLAG_RING_CACHE = 16, /* l2a_attn_decode with L2A_FLAG_SKIP_GLOBAL: the cache is a ring (see there) */
     L2A_FLAG_SCALAR = 1 << 16 /* bf16 only: use the scalar-FMA kernels instead of the matrix-core ones
-                                 (slow; for cross-checking) */
+                                 (slow; for cross-checking, and the only bf16 path for D = 64) */
 };
 
 enum {
@@ -79,7 +84,8 @@ const char* l2a_strerror(int code);
 
 /*
  * Host-only, pure: scratch bytes each call needs (0 is possible; then workspace may be NULL).
- * The workspace is device memory owned by the caller, 256-byte aligned, not preserved between
+ * The workspace is device memory owned by the caller, 16-byte aligned (sub-buffers are laid out at
+ * multiples of 256 bytes from its start), not preserved between
  * calls; calls that share one workspace must be ordered on one stream.  What it holds:
  *   route     one int32 count per (b, KV head, chunk of 2048 positions; of 256 for T <= 16384)
  *   forward   bf16, D = 128 without L2A_FLAG_SCALAR: a token-minor copy [B,Hkv,D,ceil64(T)] of
@@ -246,8 +252,9 @@ int l2a_attn_bwd(const l2a_params* p, const void* dO, const void* q_loc, const v
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Optional per-kernel timing, for benchmarks (not thread safe; off by default).  While enabled,
- * every kernel the library launches is bracketed by HIP events on the launch stream.
+ * Optional per-kernel timing, for benchmarks (off by default).  While enabled, every kernel the
+ * library launches -- from any thread: the log is guarded by a mutex, and records of concurrent
+ * callers interleave in launch order -- is bracketed by HIP events on its launch stream.
  * l2a_profile_read synchronises with those events, copies up to `max` records (launch order;
  * `name` points to a static string) into `out`, clears the log and returns the number of
  * records there were.  This log is the only state the library keeps between calls.

@@ -358,13 +358,21 @@ __device__ __forceinline__ void fwd_body(const FwdArgs& a, const int bx, const i
             run(std::true_type{}, j_begin, j_end);
     }
 
-    // ---- did every row sum stay in range?  (workgroup-wide vote; LDS is free after the last barrier)
+    // ---- did every row sum stay in range, and every accumulator finite?  (workgroup-wide vote; LDS is
+    // free after the last barrier.)  A row sum below 1e30 bounds the weights, not the products with V:
+    // values beyond ~3e8 can still overflow an accumulator, so those are checked themselves
+    // (x * 0 is NaN exactly when x is infinite or NaN).
     float lt[NQB];
     bool bad = false;
 #pragma unroll
     for (int c = 0; c < NQB; ++c) {
         lt[c] = l[c] + __shfl_xor(l[c], 32);
-        bad = bad || (wave_active && valid[c] && !(lt[c] > 0.f && lt[c] < 1.0e30f));
+        float chk = 0.f;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) chk = fmaf(oacc[d][c][e], 0.f, chk);
+        bad = bad || (wave_active && valid[c] && !(lt[c] > 0.f && lt[c] < 1.0e30f && chk == 0.f));
     }
     int* vote = reinterpret_cast<int*>(&lds_v[0][0]);
     if (threadIdx.x == 0) *vote = 0;

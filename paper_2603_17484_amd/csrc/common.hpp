@@ -31,12 +31,15 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? L2A_OK : L
 
 // Optional per-kernel timing (l2a_profile_enable / l2a_profile_read): when enabled, a KernelTimer
 // around a launch records a HIP event on the launch stream before and after it.
-void profile_begin(const char* name, hipStream_t st);
+bool profile_begin(const char* name, hipStream_t st);  // true: a record was opened (and must be closed)
 void profile_end(hipStream_t st);
 struct KernelTimer {
     hipStream_t st;
-    KernelTimer(const char* name, hipStream_t s) : st(s) { profile_begin(name, s); }
-    ~KernelTimer() { profile_end(st); }
+    bool open;
+    KernelTimer(const char* name, hipStream_t s) : st(s), open(profile_begin(name, s)) {}
+    ~KernelTimer() {
+        if (open) profile_end(st);
+    }
 };
 
 // ---- route_compact.hip

@@ -20,6 +20,8 @@ int check_params(const l2a_params* p) {
     if (G > 16) return L2A_ERR_UNSUPPORTED;
     if (p->dtype != L2A_BF16 && p->dtype != L2A_FP32) return L2A_ERR_UNSUPPORTED;
     if (p->D != 64 && p->D != 128) return L2A_ERR_UNSUPPORTED;
+    // bf16 runs on the matrix cores, built for D = 128; other head sizes only through the scalar kernels, on request
+    if (p->dtype == L2A_BF16 && p->D != 128 && !(p->flags & L2A_FLAG_SCALAR)) return L2A_ERR_UNSUPPORTED;
     if ((p->flags & L2A_FLAG_SKIP_LOCAL) && (p->flags & L2A_FLAG_SKIP_GLOBAL)) return L2A_ERR_UNSUPPORTED;
     if (!(p->softmax_scale > 0.f)) return L2A_ERR_SHAPE;
     return L2A_OK;
@@ -161,7 +163,7 @@ int l2a_attn_decode(const l2a_params* p, const void* q, const void* k_cache, con
                     void* workspace, size_t workspace_bytes, void* stream) {
     const int rc = check_params(p);
     if (rc != L2A_OK) return rc;
-    if (!use_mfma(*p) || p->Hq / p->Hkv > 32) return L2A_ERR_UNSUPPORTED;
+    if (!use_mfma(*p)) return L2A_ERR_UNSUPPORTED;  // (check_params has already limited Hq / Hkv to 16)
     const bool dense = p->flags & L2A_FLAG_DENSE;
     if (!q || !k_cache || !v_cache || !pos || !O || (!dense && !mask)) return L2A_ERR_NULL;
     const void* ptrs[] = {q, k_cache, v_cache, O, S_opt, A_opt};

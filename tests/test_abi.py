@@ -79,7 +79,18 @@ BAD = [
     (dict(B=0), -2), (dict(T=0), -2), (dict(Hq=6, Hkv=4), -2), (dict(W=-1), -2), (dict(mask_heads=3), -2),
     (dict(D=96), -3), (dict(dtype=7), -3), (dict(flags=B.L2A_FLAG_SKIP_LOCAL | B.L2A_FLAG_SKIP_GLOBAL), -3),
     (dict(softmax_scale=0.0), -2), (dict(Hq=64, Hkv=2), -3),
+    (dict(D=64), -3),      # bf16 runs on the matrix cores, built for D = 128 ...
 ]
+
+
+def test_bf16_head_size_64_only_through_the_scalar_kernels(lib):
+    """... and is accepted with L2A_FLAG_SCALAR (workspace queries answer 0 for parameters they reject)."""
+    p = B.make_params(1, 256, 4, 2, 64, 16, 1, B.L2A_BF16, 0)
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 0
+    p.flags = B.L2A_FLAG_SCALAR
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(p), 1) == 2 * 4 * 4 * 256     # the two delta arrays
+    pf = B.make_params(1, 256, 4, 2, 64, 16, 1, B.L2A_FP32, 0)
+    assert lib.l2a_attn_workspace_bytes(ctypes.byref(pf), 1) == 2 * 4 * 4 * 256
 
 
 @pytest.mark.parametrize("change,code", BAD)

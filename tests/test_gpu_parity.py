@@ -232,6 +232,30 @@ def test_bf16_scores_overflow_reference_fixup_kernel(oracle, order):
     assert redo_flags(lay).any()
 
 
+@pytest.mark.parametrize("order", SEQ)
+def test_bf16_large_values_overflow_the_accumulators_not_the_row_sums(oracle, order):
+    """Scores exceed the fixed reference by up to e^64 -- row sums near 1e29, inside the range the
+    pipelined kernel accepts -- while the values are of magnitude 1e11: the products overflow the fp32
+    output accumulators although no row sum does.  The tile must be handed to the fix-up kernel (the
+    running-maximum algorithm of App. C Alg. 1, whose weights never exceed one).  The layer is linear in
+    V, so results are compared after dividing by the values' scale."""
+    scale_v = 2.0 ** 37            # 1.4e11, a power of two: the scaled values are bf16 numbers as well
+    x = growing_scores_case(64.0)
+    ref = oracle.layer_fwd(oracle.Problem(x.q, x.k, x.v, x.mask, x.w.W))     # with values of magnitude one
+    lay = layer_from_numpy(x.q, x.k, x.v * np.float32(scale_v), x.mask, x.w.W, "bf16", order)
+    unit = layer_from_numpy(x.q, x.k, x.v, x.mask, x.w.W, "bf16", order)
+    for l_ in (lay, unit):
+        l_.route(); l_.forward()
+    torch.cuda.synchronize()
+    assert not redo_flags(unit).any(), "with values of magnitude one nothing overflows"
+    assert redo_flags(lay).any(), "overflowing accumulators must send the tile to the fix-up kernel"
+    for n in ("O", "S", "A"):
+        got = to_host(getattr(lay, n))
+        assert np.isfinite(got).all(), n
+        assert_close(n, got / scale_v, ref[n], "bf16")
+    assert_lse("lse_global", to_host(lay.lse_g), ref["lse_g"], "bf16")
+
+
 def test_bf16_scores_falling_along_sequence(oracle):
     run_and_check(oracle, growing_scores_case(-300.0), backward=False)
     run_and_check(oracle, growing_scores_case(-40.0))
