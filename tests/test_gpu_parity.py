@@ -234,12 +234,14 @@ def test_bf16_scores_overflow_reference_fixup_kernel(oracle, order):
 
 @pytest.mark.parametrize("order", SEQ)
 def test_bf16_large_values_overflow_the_accumulators_not_the_row_sums(oracle, order):
-    """Scores exceed the fixed reference by up to e^64 -- row sums near 1e29, inside the range the
-    pipelined kernel accepts -- while the values are of magnitude 1e11: the products overflow the fp32
-    output accumulators although no row sum does.  The tile must be handed to the fix-up kernel (the
+    """Scores exceed a row's fixed reference by up to e^55 in the Global branch (the reference is the largest
+    score among the tile's first 128 keys, ~64 * 128 / 900 here) and by up to e^64 in the Local branch (rows
+    none of whose keys lie in their tile's first blocks take 0) -- row sums of 1e25 and 1e29, inside the
+    range the pipelined kernel accepts -- while the values are of magnitude 1e15: the products overflow the
+    fp32 output accumulators although no row sum does.  The tile must be handed to the fix-up kernel (the
     running-maximum algorithm of App. C Alg. 1, whose weights never exceed one).  The layer is linear in
     V, so results are compared after dividing by the values' scale."""
-    scale_v = 2.0 ** 37            # 1.4e11, a power of two: the scaled values are bf16 numbers as well
+    scale_v = 2.0 ** 50            # 1.1e15, a power of two: the scaled values are bf16 numbers as well
     x = growing_scores_case(64.0)
     ref = oracle.layer_fwd(oracle.Problem(x.q, x.k, x.v, x.mask, x.w.W))     # with values of magnitude one
     lay = layer_from_numpy(x.q, x.k, x.v * np.float32(scale_v), x.mask, x.w.W, "bf16", order)
@@ -247,6 +249,8 @@ def test_bf16_large_values_overflow_the_accumulators_not_the_row_sums(oracle, or
     for l_ in (lay, unit):
         l_.route(); l_.forward()
     torch.cuda.synchronize()
+    print("tiles handed to the fix-up kernel: values of magnitude one", np.flatnonzero(redo_flags(unit)),
+          "scaled values", np.flatnonzero(redo_flags(lay)), flush=True)
     assert not redo_flags(unit).any(), "with values of magnitude one nothing overflows"
     assert redo_flags(lay).any(), "overflowing accumulators must send the tile to the fix-up kernel"
     for n in ("O", "S", "A"):
