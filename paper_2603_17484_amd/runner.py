@@ -119,5 +119,5 @@ def layer_from_numpy(q, k, v, mask, W, dtype="bf16", flags=0, scale=None, qg=Non
     Hm = 1 if mask is None else mask.shape[1]
     p = B.make_params(Bn, T, Hq, Hkv, D, W, Hm, B.L2A_BF16 if dtype == "bf16" else B.L2A_FP32, flags, scale)
     up = lambda x: None if x is None else to_device(x, dtype, device)
-    m = None if mask is None else torch.from_numpy(np.ascontiguousarray(mask, dtype=np.uint8)).to(device)
+    m = None if mask is None else torch.from_numpy(np.array(mask, dtype=np.uint8, order="C", copy=True)).to(device)
     return Layer(p, up(q), up(k), up(v), m, up(qg), up(kg), up(vg), GuardedAllocator() if guard else None)

@@ -51,9 +51,13 @@ def test_bf16_qwen_layout_8k_dense_mode_whole_tensors(oracle):
     run_and_check(oracle, x, flags=B.L2A_FLAG_DENSE, kv_heads=(0, 3), bands=True)
 
 
-def test_bf16_qwen_layout_3k_whole_tensors(oracle):
-    """The same head layout at a length that takes the split dK/dV kernel and the one-launch forward."""
-    run_and_check(oracle, make_case(T=3000, Hq=28, Hkv=4, W=700, Hm=28, f=0.2, seed=60))
+@pytest.mark.parametrize("path", ["matrix cores", "scalar"])
+def test_bf16_qwen_layout_3k_whole_tensors(oracle, path):
+    """The same head layout at a length that takes the split dK/dV kernel and the one-launch forward; and the
+    scalar-FMA kernels (fp32 arithmetic on the same bf16 storage) on the same inputs.  Both print their largest
+    gradient error per band of the row's largest reference element -- the figures behind the tolerance."""
+    flags = B.L2A_FLAG_SCALAR if path == "scalar" else 0
+    run_and_check(oracle, make_case(T=3000, Hq=28, Hkv=4, W=700, Hm=28, f=0.2, seed=60), flags=flags, bands=True)
 
 
 # ------------------------------------------------------------------------------------------
