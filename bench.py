@@ -29,8 +29,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 # committed profile are repeated here; they are reported only for exactly that workload.
 TRAFFIC_SOURCE = ("NOT measured in this run: constant copied from profiles/all_kernels_train_128k_hbm_bytes.md, two "
                   "rocprofv3 --pmc runs of `bench.py --sparse-only --calibrate-copy` on the same workload")
-MEASURED_TRAFFIC_BYTES = {"bwd_dkdv": 1.700e10, "bwd_dq_global": 1.746e10, "bwd_dq_local": 4.25e9,
-                          "fwd_global": 1.487e10, "fwd_local": 5.40e9}
+MEASURED_TRAFFIC_BYTES = {"bwd_dkdv": 1.564e10, "bwd_dq_global": 2.966e10, "bwd_dq_local": 4.25e9,
+                          "fwd_global": 2.646e10, "fwd_local": 5.44e9}
 
 
 def pair_counts(mask: np.ndarray, Hq: int, Hkv: int, T: int, W: int, dense: bool):
@@ -63,7 +63,7 @@ def main() -> int:
     ap.add_argument("--forward-only", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-step measurement")
     ap.add_argument("--sparse-only", action="store_true",
-                    help="no routed-only pass, dense mode or CPU oracle: every launch of the layer's kernels that a "
+                    help="no routed-only pass, dense mode, short-context leg or CPU oracle: every launch of the layer's kernels that a "
                          "profiler sees then belongs to the timed workload (the router and decode kernels, measured "
                          "separately, have names of their own)")
     ap.add_argument("--graph", action="store_true",
@@ -201,7 +201,8 @@ def main() -> int:
     decode = short = None
     if not args.no_decode:
         decode = decode_leg(torch, B, w, dev, g)
-        short = short_context_leg(torch, B, gen, Layer, dev, g)
+        if not args.sparse_only:   # its launches carry the layer's kernel names: kept out of profiler runs
+            short = short_context_leg(torch, B, gen, Layer, dev, g)
 
     # ---- global branch alone (routed FLOPs only)
     ms_glob = tflops_routed = None
