@@ -51,6 +51,15 @@ def test_bf16_qwen_layout_8k_dense_mode_whole_tensors(oracle):
     run_and_check(oracle, x, flags=B.L2A_FLAG_DENSE, kv_heads=(0, 3), bands=True)
 
 
+@pytest.mark.timeout(600)
+def test_bf16_batch_of_two_on_the_unsplit_path(oracle):
+    """Batch > 1 where one workgroup owns a key block: B=2, T=4096, Hq=28, Hkv=4 gives 32 key blocks x 8
+    (batch, KV head) pairs = 256 workgroups (chunks of one key block), different masks per sequence; every
+    element of two of the four KV groups, in both sequences."""
+    x = make_case(B_=2, T=4096, Hq=28, Hkv=4, W=512, Hm=28, f=0.25, seed=63)
+    run_and_check(oracle, x, kv_heads=(1, 2))
+
+
 @pytest.mark.parametrize("path", ["matrix cores", "scalar"])
 def test_bf16_qwen_layout_3k_whole_tensors(oracle, path):
     """The same head layout at a length that takes the split dK/dV kernel and the one-launch forward; and the
