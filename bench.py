@@ -267,6 +267,9 @@ def main() -> int:
             "ms_layer": round(ms_dense, 3),
             "ms_layer_graph_replay": None if ms_dense_graph is None else round(ms_dense_graph, 3),
             "speedup_sparse_vs_dense": round((ms_dense_graph or ms_dense) / ms_sparse, 3),
+            # the kernels that run on Global rows only (the dK/dV kernel walks both row sets in one launch)
+            "speedup_global_kernels": {k: round(kern_dense[k] / kern[k], 3) for k in ("fwd_global", "bwd_dq_global")
+                                       if kern.get(k) and kern_dense.get(k)},
             "tflops_layer": round(mult * D * (pl + pg_dense) / (ms_dense * 1e-3) / 1e12, 2),
             "kernels_ms": {n: round(t, 3) for n, t in kern_dense.items()}},
         "kernels_ms": {n: round(t, 3) for n, t in kern.items()},
@@ -397,7 +400,8 @@ def cpu_baseline(w, q, k, v, dO, mask_np, backward, seed, budget_s=15.0):
             "sample": f"{n} routed rows drawn uniformly: oracle forward (local+global) "
                       f"{'and dQ pass ' if backward else ''}over {pairs:.3e} (row,key) pairs in {dt:.1f} s; "
                       f"{'no dK/dV pass is run; ' if backward else ''}valued at {per_pair / w.D:.0f} D FLOP per pair "
-                      f"(forward 4 D{', dP and dQ 4 D' if backward else ''})"}
+                      f"(forward 4 D{', dP and dQ 4 D' if backward else ''})",
+            "ns_per_row_key_pair": round(dt * 1e9 / pairs, 3)}
 
 
 if __name__ == "__main__":
