@@ -140,11 +140,16 @@ def main() -> int:
         if profile:
             B.profile_read()
             B.profile_enable(True)
+        # one event per step boundary on the launch stream (recording does not synchronise): the spread of the steps
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
-        for _ in range(steps):
+        marks[0].record()
+        for i in range(steps):
             step(lay)
+            marks[i + 1].record()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / steps
+        timed.per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
         kern = {}
         if profile:
             B.profile_enable(False)
@@ -163,6 +168,7 @@ def main() -> int:
     # (the per-kernel HIP events cost a few microseconds per launch: they are recorded in a pass of their own)
     sparse = build(0)
     ms_sparse, _ = timed(sparse, args.steps, args.warmup)
+    per_step = sorted(timed.per_step)
     _, kern = timed(sparse, max(1, min(args.steps, 5)), 0, profile=True)
     ms_eager = None
     if args.graph:
@@ -257,6 +263,7 @@ def main() -> int:
                    "mask": f"{w.mask_kind}, mask_heads={w.mask_heads}", "routed_fraction_measured": round(frac, 4),
                    "passes": "fwd+bwd" if backward else "fwd", "seed": args.seed},
         "ms_layer": round(ms_sparse, 3),
+        "ms_per_step_min": round(per_step[0], 3), "ms_per_step_median": round(float(np.median(per_step)), 3),
         "launch": "hip graph replay" if args.graph else "eager",
         "ms_layer_eager": None if ms_eager is None else round(ms_eager, 3),
         "frac_of_bf16_peak_layer": round(tflops_layer / PEAK_BF16_TFLOPS, 4),
